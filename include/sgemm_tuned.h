@@ -1,0 +1,232 @@
+/*
+ * sgemm_tuned.h — C ABI of the auto-tuned single-precision GEMM for AMD MI355X (gfx950).
+ *
+ * The library holds a family of GEMM kernels generated from one HIP source by compile-time
+ * parameters, the tuner that searches that parameter space (full, random, simulated
+ * annealing, particle swarm), and a per-shape cache of the best configuration found.
+ * It follows the auto-tuning method of the CLTune paper (sections "CLTune: an auto-tuner
+ * for OpenCL kernels" and "Case-study: matrix-multiplication"), redesigned for gfx950.
+ *
+ * Conventions for every entry point
+ *   - All functions are extern "C", never throw, and return an int status: SGEMM_OK (0) or
+ *     a negative SGEMM_E_* code (sgemm_status_string() names it).  Functions documented as
+ *     returning a count return a value >= 0 on success.
+ *   - A, B, C are DEVICE pointers (for example torch.Tensor.data_ptr() on a ROCm tensor).
+ *     The caller owns them; the library never frees or keeps them.
+ *   - Everything else (config structs, tables, strings, result structs) is HOST memory
+ *     owned by the caller.
+ *   - Launches are asynchronous on the given HIP stream; an error detected by the launch
+ *     call is returned, a later device fault is not.
+ *   - Functions marked [host] need no GPU and touch no GPU state.
+ */
+#ifndef SGEMM_TUNED_H
+#define SGEMM_TUNED_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---- status codes ---------------------------------------------------------------- */
+#define SGEMM_OK 0
+#define SGEMM_E_BADARG (-1)   /* negative size, leading dimension too small, null pointer
+                                 for a non-empty operand, unknown layout/strategy/preset */
+#define SGEMM_E_NOCONFIG (-2) /* the search space holds no valid configuration */
+#define SGEMM_E_COMPILE (-3)  /* the kernel generator failed to compile a variant */
+#define SGEMM_E_LAUNCH (-4)   /* HIP refused a module load, launch, allocation or copy */
+#define SGEMM_E_VERIFY (-5)   /* a variant's output disagreed with the reference kernel */
+#define SGEMM_E_INVALID (-6)  /* configuration violates a constraint of the kernel family */
+#define SGEMM_E_IO (-7)       /* cache file could not be read or written */
+#define SGEMM_E_NODEVICE (-8) /* no usable HIP device */
+#define SGEMM_E_RESOURCE (-9) /* variant compiled but spills registers or exceeds LDS */
+
+/* ---- layout bits ------------------------------------------------------------------
+ * The paper's kernel multiplies A^T by B, i.e. it expects A stored K x M.  Here that
+ * storage is selected per call: bit 0 set = A stored K x M (row-major, lda >= M), clear =
+ * A stored M x K (lda >= K); bit 1 set = B stored N x K (ldb >= K), clear = B stored K x N
+ * (ldb >= N).  C is always M x N row-major (ldc >= N).  Leading dimensions in elements. */
+#define SGEMM_LAYOUT_A_TRANSPOSED 1
+#define SGEMM_LAYOUT_B_TRANSPOSED 2
+
+/* ---- search strategies (section "Search strategies and search-space properties") ---- */
+#define SGEMM_STRATEGY_FULL 0
+#define SGEMM_STRATEGY_RANDOM 1
+#define SGEMM_STRATEGY_ANNEALING 2
+#define SGEMM_STRATEGY_PSO 3
+
+/* ---- search-space presets ---------------------------------------------------------- */
+#define SGEMM_SPACE_FULL 0  /* the full gfx950 space (about 10^4 valid configurations) */
+#define SGEMM_SPACE_SMALL 1 /* 16 configurations: MWG,NWG in {32,64}, KWG in {8,16},
+                               LDS staging on/off; everything else fixed */
+#define SGEMM_SPACE_MFMA 2  /* matrix-core variants only, both operands staged, wider value
+                               lists (workgroups up to 512 threads, both MFMA shapes) */
+
+/* One point of the parameter space.  Names follow the paper's GEMM parameters (list in
+ * "Tuning parameters" of the matrix-multiplication case study): the workgroup tile
+ * Mwg/Nwg/Kwg, the workgroup shape MdimC x NdimC (so each thread owns Mwi = Mwg/MdimC by
+ * Nwi = Nwg/NdimC accumulators), the vector widths of the off-chip loads, local-memory
+ * staging per operand, and the unroll factor Kwi of the Kwg loop.  `pad`, `mfma` and `grp`
+ * are gfx950 additions.  All fields are plain ints so the struct is an int[16]. */
+typedef struct sgemm_config {
+    int mwg, nwg, kwg; /* workgroup macro-tile of C (mwg x nwg) and K slab per step      */
+    int mdimc, ndimc;  /* threads per workgroup = mdimc * ndimc (multiple of 64)         */
+    int vwm;           /* floats per global load of A (1, 2, 4)                          */
+    int vwn;           /* floats per global load of B and per store of C (1, 2, 4)       */
+    int sa, sb;        /* 1 = stage A / B tiles through LDS (double-buffered), 0 = read
+                          operands straight from global memory                            */
+    int pad;           /* 1 = pad LDS rows by 4 floats (bank-conflict-free fragment reads) */
+    int kwi;           /* the KWG loop advances kwi at a time, body unrolled (2 or 8)     */
+    int mfma;          /* 0 = per-thread register tile on the vector ALU,
+                          1 = v_mfma_f32_32x32x2_f32 wave tiles,
+                          2 = v_mfma_f32_16x16x4_f32 wave tiles                           */
+    int grp;           /* 1 = XCD-aware workgroup-to-tile order, 0 = row-major order      */
+    int reserved[3];   /* must be 0                                                        */
+} sgemm_config;
+
+/* What the generator knows about one compiled variant. */
+typedef struct sgemm_kernel_info {
+    int vgprs;         /* architected VGPRs per lane                                      */
+    int agprs;         /* accumulation VGPRs per lane                                     */
+    int sgprs;
+    int lds_bytes;     /* static LDS per workgroup                                        */
+    int scratch_bytes; /* private segment per lane; > 0 means register spills             */
+    int code_bytes;    /* size of the code object                                         */
+    int from_cache;    /* 1 = read from the on-disk cache, 0 = compiled now               */
+    float compile_ms;
+} sgemm_kernel_info;
+
+/* Options of tune_ex(); zero-initialise and set what you need (0 = default). */
+typedef struct tune_opts {
+    int space;          /* SGEMM_SPACE_*; 0 = SGEMM_SPACE_FULL                            */
+    int warmup;         /* untimed launches per configuration; default 2                  */
+    int reps;           /* timed samples per configuration (median is kept); default 7    */
+    int verify_off;     /* 1 = skip the comparison against the reference kernel           */
+    float cut_factor;   /* stop timing a configuration whose first sample is slower than
+                           cut_factor x the best so far and keep that sample as its time;
+                           default 3, negative = never cut                                 */
+    float sa_T;         /* annealing temperature (paper: 2, 4, 6); default 4              */
+    int sa_raw_ms;      /* 1 = t, t' in raw milliseconds; 0 = percent of best-so-far      */
+    int pso_S;          /* swarm size (paper: 3, 6); default 3                            */
+    float pso_alpha;    /* probability of a random value per dimension; default 0.4       */
+    float pso_beta;     /* probability of the particle's own best; default 0              */
+    float pso_gamma;    /* probability of the swarm's best; default 0.4                   */
+    float random_fraction; /* random search: fraction of the space if budget <= 0         */
+    const float *A;     /* optional caller-owned DEVICE operands in the call's layout;    */
+    const float *B;     /*   when A is null the library allocates seeded synthetic ones   */
+    float *C;           /*   (C is overwritten; C_in is restored from C0 before each run) */
+    const float *C0;    /* optional DEVICE copy of the initial C (needed when beta != 0)  */
+    int lda, ldb, ldc;
+    const char *log_path; /* optional HOST path: one JSON line appended per evaluation    */
+    int reserved[8];
+} tune_opts;
+
+typedef struct tune_result {
+    sgemm_config best;
+    float best_ms;       /* median milliseconds of the best configuration                  */
+    float best_gflops;   /* 2*M*N*K / best_ms                                              */
+    int best_index;      /* its index in the enumerated space                              */
+    int evaluations;     /* distinct configurations timed                                  */
+    int failed;          /* of those: failed to compile, spilled or failed verification    */
+    int space_size;      /* valid configurations in the space                              */
+    int evals_to_best;   /* evaluations made when the best was first timed                 */
+    float total_ms;      /* wall time of the whole search                                  */
+    float compile_ms;    /* of which kernel generation                                      */
+    int reserved[6];
+} tune_result;
+
+/* ---- the GEMM call ------------------------------------------------------------------
+ * C = alpha * op(A) * op(B) + beta * C   (first equation of the matrix-multiplication case
+ * study; `layout` says how A and B are stored, see above).
+ * M, N, K >= 0.  M == 0 or N == 0: no-op.  K == 0 or alpha == 0: C = beta * C and A, B are
+ * not read.  beta == 0: C is written without being read, so NaN/Inf in it do not propagate.
+ * The variant is the cached best configuration for (M,N,K,layout); on a miss, the cached
+ * configuration of the nearest tuned shape that is valid here, else a built-in default.
+ * This call never tunes.  A variant not yet in the kernel cache is compiled on first use.
+ * sgemm_tuned() launches on the stream given to sgemm_set_stream() (default: null stream). */
+int sgemm_tuned(int M, int N, int K, float alpha, const float *A, int lda, const float *B,
+                int ldb, float beta, float *C, int ldc, int layout);
+int sgemm_tuned_on(void *hip_stream, int M, int N, int K, float alpha, const float *A, int lda,
+                   const float *B, int ldb, float beta, float *C, int ldc, int layout);
+int sgemm_set_stream(void *hip_stream);
+
+/* Same operation with an explicit configuration (what the tuner times and the parity tests
+ * drive).  Returns SGEMM_E_INVALID if `cfg` breaks a constraint; picks the guarded-edge
+ * build of the variant when M, N, K are not multiples of the tile, and narrows vwm/vwn to 1
+ * when a pointer or leading dimension is not aligned for the vector width. */
+int sgemm_run_config(void *hip_stream, const sgemm_config *cfg, int M, int N, int K,
+                     float alpha, const float *A, int lda, const float *B, int ldb, float beta,
+                     float *C, int ldc, int layout);
+
+/* The reference kernel every tested configuration is compared with inside tune*() (the
+ * paper's result verification, section "Advanced usage"): one thread per element of C,
+ * products and sums in double, result rounded to float.  Exported so that tests can check it. */
+int sgemm_reference(void *hip_stream, int M, int N, int K, float alpha, const float *A, int lda,
+                    const float *B, int ldb, float beta, float *C, int ldc, int layout);
+
+/* ---- tuning -------------------------------------------------------------------------
+ * tune(): search the full space for (M,N,K), row-major A and B, alpha = 1, beta = 0, on
+ * library-owned synthetic operands; store the winner in the per-shape cache.  `strategy` is
+ * SGEMM_STRATEGY_*; `budget` = maximum number of distinct configurations timed (ignored by
+ * the full search).  Returns the number of configurations evaluated (>= 0) or an error.
+ * tune_ex(): the same with everything explicit; fills *out (may be null). */
+int tune(int M, int N, int K, int strategy, int budget);
+int tune_ex(int M, int N, int K, int layout, float alpha, float beta, int strategy, int budget,
+            unsigned long long seed, const tune_opts *opts, tune_result *out);
+
+/* [host] Run a strategy against a table of known costs instead of the GPU: ms_table[i] is
+ * the time of configuration i of `space` (a non-finite or non-positive entry marks a failed
+ * configuration).  visited (may be null) receives up to visited_cap configuration indices in
+ * evaluation order.  This is how recorded full searches are replayed for strategy studies
+ * (the paper repeats every search 128 times).  Returns evaluations made or an error. */
+int tune_replay(int space, const float *ms_table, int table_len, int strategy, int budget,
+                unsigned long long seed, const tune_opts *opts, int *visited, int visited_cap,
+                tune_result *out);
+
+/* ---- search space [host] ------------------------------------------------------------- */
+int sgemm_space_size(int space);      /* valid configurations after constraint pruning     */
+long long sgemm_space_raw_size(int space); /* plain product of the value-list lengths      */
+int sgemm_space_get(int space, int index, sgemm_config *out);
+int sgemm_space_find(int space, const sgemm_config *cfg); /* index, or SGEMM_E_INVALID     */
+int sgemm_space_dims(int space);      /* number of tuned parameters                        */
+/* values of parameter `dim` (0-based, in sgemm_config field order); returns the count */
+int sgemm_space_values(int space, int dim, int *values, int cap);
+/* SGEMM_OK if cfg satisfies every constraint of the kernel family (divisibility, thread
+ * count, register budget, LDS capacity), else SGEMM_E_INVALID. */
+int sgemm_config_check(const sgemm_config *cfg);
+int sgemm_config_lds_bytes(const sgemm_config *cfg); /* LDS the variant will declare       */
+int sgemm_config_default(int M, int N, int K, int layout, sgemm_config *out);
+
+/* ---- kernel generator --------------------------------------------------------------- */
+/* [host] Directory of the on-disk code-object cache (default: "kcache" beside the library,
+ * or $SGEMM_TUNED_CACHE_DIR). */
+int sgemm_kernel_cache_dir(const char *path);
+/* [host] Compile (or fetch from the cache) the variant for cfg/layout; edge = 1 builds the
+ * bounds-guarded form.  Needs no GPU.  info may be null. */
+int sgemm_kernel_compile(const sgemm_config *cfg, int layout, int edge, sgemm_kernel_info *info);
+/* [host] The -D macro string the variant is compiled with, NUL-terminated into buf. */
+int sgemm_kernel_macros(const sgemm_config *cfg, int layout, int edge, char *buf, int cap);
+
+/* ---- per-shape best-configuration cache --------------------------------------------- */
+int sgemm_config_get(int M, int N, int K, int layout, sgemm_config *out); /* exact shape only;
+                                         SGEMM_E_NOCONFIG on a miss */
+int sgemm_config_set(int M, int N, int K, int layout, const sgemm_config *cfg, float ms);
+int sgemm_config_select(int M, int N, int K, int layout, sgemm_config *out); /* what
+                                         sgemm_tuned() would use: exact, nearest, default */
+int sgemm_cache_load(const char *path); /* merge a text file into the cache               */
+int sgemm_cache_save(const char *path);
+int sgemm_cache_clear(void);
+int sgemm_cache_count(void);
+
+/* ---- device facts ------------------------------------------------------------------- */
+/* FP32 peak in GFLOP/s = compute units x 256 FLOP/clk x clock, from the device's own
+ * properties; also returns CU count and clock (MHz) if the pointers are non-null. */
+int sgemm_device_peak(float *gflops, int *compute_units, int *clock_mhz);
+
+const char *sgemm_status_string(int status);
+/* Detail of the calling thread's most recent failure (compiler log, HIP error string); the
+ * pointer stays valid until that thread's next failing call.  Never null. */
+const char *sgemm_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SGEMM_TUNED_H */

@@ -1,0 +1,344 @@
+"""ctypes binding of the C-ABI library (include/sgemm_tuned.h): argument marshalling only.
+Every function has the name of the C entry point it calls.  PyTorch appears only where a
+caller passes tensors: their data_ptr() and the current HIP stream are handed to the library.
+
+The library must have been built (paper_1703_06503_amd/build.py); loading fails loudly
+otherwise, and there is no fallback path of any kind."""
+import ctypes
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "lib", "libsgemm_tuned.so")
+
+OK = 0
+E_BADARG, E_NOCONFIG, E_COMPILE, E_LAUNCH, E_VERIFY = -1, -2, -3, -4, -5
+E_INVALID, E_IO, E_NODEVICE, E_RESOURCE = -6, -7, -8, -9
+LAYOUT_A_TRANSPOSED, LAYOUT_B_TRANSPOSED = 1, 2
+STRATEGY_FULL, STRATEGY_RANDOM, STRATEGY_ANNEALING, STRATEGY_PSO = 0, 1, 2, 3
+SPACE_FULL, SPACE_SMALL, SPACE_MFMA = 0, 1, 2
+
+CONFIG_FIELDS = ("mwg", "nwg", "kwg", "mdimc", "ndimc", "vwm", "vwn", "sa", "sb", "pad", "kwi",
+                 "mfma", "grp")
+
+
+class sgemm_config(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int) for n in CONFIG_FIELDS] + [("reserved", ctypes.c_int * 3)]
+
+    def as_tuple(self):
+        return tuple(getattr(self, n) for n in CONFIG_FIELDS)
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n in CONFIG_FIELDS}
+
+    def __repr__(self):
+        return "sgemm_config(" + ", ".join(f"{n}={getattr(self, n)}" for n in CONFIG_FIELDS) + ")"
+
+
+def make_config(*args, **kw):
+    """sgemm_config from 13 positional values in field order, or from keywords."""
+    c = sgemm_config()
+    if args:
+        if len(args) != len(CONFIG_FIELDS):
+            raise ValueError("expected %d values" % len(CONFIG_FIELDS))
+        kw = dict(zip(CONFIG_FIELDS, args))
+    for k, v in kw.items():
+        if k not in CONFIG_FIELDS:
+            raise ValueError(f"unknown field {k}")
+        setattr(c, k, int(v))
+    return c
+
+
+class sgemm_kernel_info(ctypes.Structure):
+    _fields_ = [("vgprs", ctypes.c_int), ("agprs", ctypes.c_int), ("sgprs", ctypes.c_int),
+                ("lds_bytes", ctypes.c_int), ("scratch_bytes", ctypes.c_int),
+                ("code_bytes", ctypes.c_int), ("from_cache", ctypes.c_int),
+                ("compile_ms", ctypes.c_float)]
+
+
+class tune_opts(ctypes.Structure):
+    _fields_ = [("space", ctypes.c_int), ("warmup", ctypes.c_int), ("reps", ctypes.c_int),
+                ("verify_off", ctypes.c_int), ("cut_factor", ctypes.c_float),
+                ("sa_T", ctypes.c_float), ("sa_raw_ms", ctypes.c_int), ("pso_S", ctypes.c_int),
+                ("pso_alpha", ctypes.c_float), ("pso_beta", ctypes.c_float),
+                ("pso_gamma", ctypes.c_float), ("random_fraction", ctypes.c_float),
+                ("A", ctypes.c_void_p), ("B", ctypes.c_void_p), ("C", ctypes.c_void_p),
+                ("C0", ctypes.c_void_p), ("lda", ctypes.c_int), ("ldb", ctypes.c_int),
+                ("ldc", ctypes.c_int), ("log_path", ctypes.c_char_p),
+                ("reserved", ctypes.c_int * 8)]
+
+
+class tune_result(ctypes.Structure):
+    _fields_ = [("best", sgemm_config), ("best_ms", ctypes.c_float),
+                ("best_gflops", ctypes.c_float), ("best_index", ctypes.c_int),
+                ("evaluations", ctypes.c_int), ("failed", ctypes.c_int),
+                ("space_size", ctypes.c_int), ("evals_to_best", ctypes.c_int),
+                ("total_ms", ctypes.c_float), ("compile_ms", ctypes.c_float),
+                ("reserved", ctypes.c_int * 6)]
+
+
+EXPORTS = (
+    "sgemm_tuned", "sgemm_tuned_on", "sgemm_set_stream", "sgemm_run_config", "sgemm_reference",
+    "tune", "tune_ex", "tune_replay", "sgemm_space_size", "sgemm_space_raw_size",
+    "sgemm_space_get", "sgemm_space_find", "sgemm_space_dims", "sgemm_space_values",
+    "sgemm_config_check", "sgemm_config_lds_bytes", "sgemm_config_default",
+    "sgemm_kernel_cache_dir", "sgemm_kernel_compile", "sgemm_kernel_macros", "sgemm_config_get",
+    "sgemm_config_set", "sgemm_config_select", "sgemm_cache_load", "sgemm_cache_save",
+    "sgemm_cache_clear", "sgemm_cache_count", "sgemm_device_peak", "sgemm_status_string",
+    "sgemm_last_error",
+)
+
+_lib = None
+
+
+def lib():
+    """The loaded shared library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_1703_06503_amd.build` "
+                               "(there is no fallback implementation)")
+        # One HIP runtime per process: the device pointers and streams handed to the library
+        # come from PyTorch, so the library must resolve libamdhip64 / libhiprtc to the copies
+        # PyTorch bundles (same SONAMEs as the system ones) rather than load a second runtime.
+        import torch
+        torch_lib = os.path.join(os.path.dirname(torch.__file__), "lib")
+        for name in ("libamdhip64.so", "libhiprtc.so"):
+            path = os.path.join(torch_lib, name)
+            if os.path.exists(path):
+                ctypes.CDLL(path, mode=ctypes.RTLD_GLOBAL)
+        L = ctypes.CDLL(LIB_PATH)
+        i, f, vp = ctypes.c_int, ctypes.c_float, ctypes.c_void_p
+        cfgp = ctypes.POINTER(sgemm_config)
+        gemm = [i, i, i, f, vp, i, vp, i, f, vp, i, i]
+        L.sgemm_tuned.argtypes = gemm
+        L.sgemm_tuned_on.argtypes = [vp] + gemm
+        L.sgemm_set_stream.argtypes = [vp]
+        L.sgemm_run_config.argtypes = [vp, cfgp] + gemm
+        L.sgemm_reference.argtypes = [vp] + gemm
+        L.tune.argtypes = [i, i, i, i, i]
+        L.tune_ex.argtypes = [i, i, i, i, f, f, i, i, ctypes.c_ulonglong,
+                              ctypes.POINTER(tune_opts), ctypes.POINTER(tune_result)]
+        L.tune_replay.argtypes = [i, ctypes.POINTER(f), i, i, i, ctypes.c_ulonglong,
+                                  ctypes.POINTER(tune_opts), ctypes.POINTER(i), i,
+                                  ctypes.POINTER(tune_result)]
+        L.sgemm_space_size.argtypes = [i]
+        L.sgemm_space_raw_size.argtypes = [i]
+        L.sgemm_space_raw_size.restype = ctypes.c_longlong
+        L.sgemm_space_get.argtypes = [i, i, cfgp]
+        L.sgemm_space_find.argtypes = [i, cfgp]
+        L.sgemm_space_dims.argtypes = [i]
+        L.sgemm_space_values.argtypes = [i, i, ctypes.POINTER(i), i]
+        L.sgemm_config_check.argtypes = [cfgp]
+        L.sgemm_config_lds_bytes.argtypes = [cfgp]
+        L.sgemm_config_default.argtypes = [i, i, i, i, cfgp]
+        L.sgemm_kernel_cache_dir.argtypes = [ctypes.c_char_p]
+        L.sgemm_kernel_compile.argtypes = [cfgp, i, i, ctypes.POINTER(sgemm_kernel_info)]
+        L.sgemm_kernel_macros.argtypes = [cfgp, i, i, ctypes.c_char_p, i]
+        L.sgemm_config_get.argtypes = [i, i, i, i, cfgp]
+        L.sgemm_config_set.argtypes = [i, i, i, i, cfgp, f]
+        L.sgemm_config_select.argtypes = [i, i, i, i, cfgp]
+        L.sgemm_cache_load.argtypes = [ctypes.c_char_p]
+        L.sgemm_cache_save.argtypes = [ctypes.c_char_p]
+        L.sgemm_cache_clear.argtypes = []
+        L.sgemm_cache_count.argtypes = []
+        L.sgemm_device_peak.argtypes = [ctypes.POINTER(f), ctypes.POINTER(i), ctypes.POINTER(i)]
+        L.sgemm_status_string.argtypes = [i]
+        L.sgemm_status_string.restype = ctypes.c_char_p
+        L.sgemm_last_error.argtypes = []
+        L.sgemm_last_error.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+class SgemmError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = status
+        detail = sgemm_last_error()
+        super().__init__(f"{what}: {sgemm_status_string(status)} ({status})"
+                         + (f": {detail}" if detail else ""))
+
+
+def _check(status, what):
+    if status < 0:
+        raise SgemmError(status, what)
+    return status
+
+
+def sgemm_status_string(status):
+    return lib().sgemm_status_string(int(status)).decode()
+
+
+def sgemm_last_error():
+    return lib().sgemm_last_error().decode(errors="replace")
+
+
+def _ptr(t):
+    """Device address of a torch tensor (or a raw int / None)."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def sgemm_tuned(M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, layout=0):
+    return _check(lib().sgemm_tuned(M, N, K, alpha, _ptr(A), lda, _ptr(B), ldb, beta, _ptr(C),
+                                    ldc, layout), "sgemm_tuned")
+
+
+def sgemm_tuned_on(stream, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, layout=0):
+    return _check(lib().sgemm_tuned_on(_stream(stream), M, N, K, alpha, _ptr(A), lda, _ptr(B),
+                                       ldb, beta, _ptr(C), ldc, layout), "sgemm_tuned_on")
+
+
+def sgemm_set_stream(stream):
+    return _check(lib().sgemm_set_stream(_stream(stream)), "sgemm_set_stream")
+
+
+def sgemm_run_config(stream, cfg, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, layout=0):
+    return _check(lib().sgemm_run_config(_stream(stream), ctypes.byref(cfg), M, N, K, alpha,
+                                         _ptr(A), lda, _ptr(B), ldb, beta, _ptr(C), ldc, layout),
+                  "sgemm_run_config")
+
+
+def sgemm_reference(stream, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, layout=0):
+    return _check(lib().sgemm_reference(_stream(stream), M, N, K, alpha, _ptr(A), lda, _ptr(B),
+                                        ldb, beta, _ptr(C), ldc, layout), "sgemm_reference")
+
+
+def tune(M, N, K, strategy, budget):
+    return _check(lib().tune(M, N, K, strategy, budget), "tune")
+
+
+def tune_ex(M, N, K, layout, alpha, beta, strategy, budget, seed=0, opts=None):
+    """Returns (evaluations, tune_result)."""
+    res = tune_result()
+    n = _check(lib().tune_ex(M, N, K, layout, alpha, beta, strategy, budget, seed,
+                             ctypes.byref(opts) if opts is not None else None,
+                             ctypes.byref(res)), "tune_ex")
+    return n, res
+
+
+def tune_replay(space, ms_table, strategy, budget, seed=0, opts=None):
+    """Returns (evaluations, tune_result, visited indices)."""
+    n = len(ms_table)
+    table = (ctypes.c_float * n)(*ms_table)
+    visited = (ctypes.c_int * n)()
+    res = tune_result()
+    ev = _check(lib().tune_replay(space, table, n, strategy, budget, seed,
+                                  ctypes.byref(opts) if opts is not None else None, visited, n,
+                                  ctypes.byref(res)), "tune_replay")
+    return ev, res, list(visited[:ev])
+
+
+def sgemm_space_size(space):
+    return _check(lib().sgemm_space_size(space), "sgemm_space_size")
+
+
+def sgemm_space_raw_size(space):
+    return _check(lib().sgemm_space_raw_size(space), "sgemm_space_raw_size")
+
+
+def sgemm_space_get(space, index):
+    c = sgemm_config()
+    _check(lib().sgemm_space_get(space, index, ctypes.byref(c)), "sgemm_space_get")
+    return c
+
+
+def sgemm_space_find(space, cfg):
+    return lib().sgemm_space_find(space, ctypes.byref(cfg))
+
+
+def sgemm_space_dims(space):
+    return _check(lib().sgemm_space_dims(space), "sgemm_space_dims")
+
+
+def sgemm_space_values(space, dim):
+    buf = (ctypes.c_int * 16)()
+    n = _check(lib().sgemm_space_values(space, dim, buf, 16), "sgemm_space_values")
+    return list(buf[:n])
+
+
+def sgemm_config_check(cfg):
+    return lib().sgemm_config_check(ctypes.byref(cfg))
+
+
+def sgemm_config_lds_bytes(cfg):
+    return _check(lib().sgemm_config_lds_bytes(ctypes.byref(cfg)), "sgemm_config_lds_bytes")
+
+
+def sgemm_config_default(M, N, K, layout=0):
+    c = sgemm_config()
+    _check(lib().sgemm_config_default(M, N, K, layout, ctypes.byref(c)), "sgemm_config_default")
+    return c
+
+
+def sgemm_kernel_cache_dir(path):
+    return _check(lib().sgemm_kernel_cache_dir(os.fsencode(path)), "sgemm_kernel_cache_dir")
+
+
+def sgemm_kernel_compile(cfg, layout=0, edge=0):
+    info = sgemm_kernel_info()
+    _check(lib().sgemm_kernel_compile(ctypes.byref(cfg), layout, edge, ctypes.byref(info)),
+           "sgemm_kernel_compile")
+    return info
+
+
+def sgemm_kernel_macros(cfg, layout=0, edge=0):
+    buf = ctypes.create_string_buffer(512)
+    _check(lib().sgemm_kernel_macros(ctypes.byref(cfg), layout, edge, buf, 512),
+           "sgemm_kernel_macros")
+    return buf.value.decode()
+
+
+def sgemm_config_get(M, N, K, layout=0):
+    c = sgemm_config()
+    st = lib().sgemm_config_get(M, N, K, layout, ctypes.byref(c))
+    if st == E_NOCONFIG:
+        return None
+    _check(st, "sgemm_config_get")
+    return c
+
+
+def sgemm_config_set(M, N, K, layout, cfg, ms=0.0):
+    return _check(lib().sgemm_config_set(M, N, K, layout, ctypes.byref(cfg), ms),
+                  "sgemm_config_set")
+
+
+def sgemm_config_select(M, N, K, layout=0):
+    c = sgemm_config()
+    _check(lib().sgemm_config_select(M, N, K, layout, ctypes.byref(c)), "sgemm_config_select")
+    return c
+
+
+def sgemm_cache_load(path):
+    return _check(lib().sgemm_cache_load(os.fsencode(path)), "sgemm_cache_load")
+
+
+def sgemm_cache_save(path):
+    return _check(lib().sgemm_cache_save(os.fsencode(path)), "sgemm_cache_save")
+
+
+def sgemm_cache_clear():
+    return _check(lib().sgemm_cache_clear(), "sgemm_cache_clear")
+
+
+def sgemm_cache_count():
+    return _check(lib().sgemm_cache_count(), "sgemm_cache_count")
+
+
+def sgemm_device_peak():
+    """(FP32 peak in GFLOP/s, compute units, clock in MHz) of the current device."""
+    g, cu, mhz = ctypes.c_float(), ctypes.c_int(), ctypes.c_int()
+    _check(lib().sgemm_device_peak(ctypes.byref(g), ctypes.byref(cu), ctypes.byref(mhz)),
+           "sgemm_device_peak")
+    return g.value, cu.value, mhz.value

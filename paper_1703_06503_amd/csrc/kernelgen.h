@@ -1,0 +1,51 @@
+// Kernel generator: turns one configuration into a gfx950 code object by compiling the
+// embedded kernel source with the configuration as -D macros (hipRTC), keeps code objects in
+// an on-disk cache, and loads them as HIP modules.  The paper recompiles its kernel once per
+// configuration in the same way (section "CLTune: an auto-tuner for OpenCL kernels") and
+// notes that recompilation can dominate tuning time ("Search strategies ..."): hence the cache.
+#pragma once
+#include <hip/hip_runtime_api.h>
+
+#include <memory>
+#include <string>
+#include <vector>
+
+#include "../../include/sgemm_tuned.h"
+
+namespace sgemm {
+
+// The variant actually built for a call: configuration + storage layout + guarded or not.
+struct VariantKey {
+    sgemm_config cfg;
+    int layout;
+    int edge;
+    std::string macros() const; // "-DMWG=.. -DNWG=.. ..." in a fixed order
+};
+
+struct CodeObject {
+    std::vector<char> image;
+    sgemm_kernel_info info{};
+};
+
+// Compile or fetch from the disk cache.  Needs no GPU.  On failure returns SGEMM_E_COMPILE
+// and, if log is non-null, the compiler's message.
+int get_code_object(const VariantKey &key, CodeObject *out, std::string *log);
+
+void set_cache_dir(const std::string &path);
+std::string cache_dir();
+
+// A loaded variant; unloads its module when destroyed.
+struct LoadedKernel {
+    hipModule_t module = nullptr;
+    hipFunction_t fn = nullptr;
+    sgemm_kernel_info info{};
+    int threads = 0;
+    ~LoadedKernel();
+};
+
+int load_kernel(const VariantKey &key, std::shared_ptr<LoadedKernel> *out, std::string *log);
+
+// Reads vgpr/agpr/sgpr counts and LDS/scratch sizes from a code object's metadata note.
+void read_code_object_info(const std::vector<char> &image, sgemm_kernel_info *info);
+
+} // namespace sgemm

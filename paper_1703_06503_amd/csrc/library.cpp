@@ -1,0 +1,681 @@
+// The C ABI of the tuned SGEMM library: dispatch of a GEMM call to a generated variant, the
+// tuning harness (fresh operands, verification against the reference kernel, warm-up and
+// median-of-N timing), the per-shape best-configuration cache, and the host-only queries.
+#include <dlfcn.h>
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <chrono>
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <map>
+#include <memory>
+#include <mutex>
+#include <string>
+#include <tuple>
+#include <vector>
+
+#include "../../include/sgemm_tuned.h"
+#include "kernelgen.h"
+#include "space.h"
+#include "strategy.h"
+#include "util_kernels.h"
+
+using namespace sgemm;
+
+namespace {
+
+thread_local std::string t_last_error; // detail of the calling thread's last failure
+
+void set_error(const std::string &what) {
+    t_last_error = what;
+    if (std::getenv("SGEMM_TUNED_VERBOSE")) std::fprintf(stderr, "sgemm_tuned: %s\n", what.c_str());
+}
+
+std::mutex g_mu;                  // guards everything below
+hipStream_t g_stream = nullptr;   // stream of sgemm_tuned()
+std::map<std::string, std::shared_ptr<LoadedKernel>> g_loaded; // by macro string
+constexpr size_t kMaxLoaded = 1024;
+
+struct Tuned {
+    sgemm_config cfg;
+    float ms;
+};
+using ShapeKey = std::tuple<int, int, int, int>; // M, N, K, layout
+std::map<ShapeKey, Tuned> g_tuned;
+bool g_tuned_autoloaded = false;
+
+std::string library_dir() {
+    Dl_info info;
+    if (dladdr((const void *)&library_dir, &info) && info.dli_fname) {
+        std::string p = info.dli_fname;
+        const size_t slash = p.find_last_of('/');
+        return (slash == std::string::npos) ? "." : p.substr(0, slash);
+    }
+    return ".";
+}
+
+int load_cache_file_locked(const char *path) {
+    FILE *f = std::fopen(path, "r");
+    if (!f) return SGEMM_E_IO;
+    char line[512];
+    int added = 0;
+    while (std::fgets(line, sizeof line, f)) {
+        if (line[0] == '#' || line[0] == '\n') continue;
+        int M, N, K, layout;
+        float ms;
+        Point p;
+        const int got = std::sscanf(line, "%d %d %d %d %f %d %d %d %d %d %d %d %d %d %d %d %d %d", &M,
+                                    &N, &K, &layout, &ms, &p[0], &p[1], &p[2], &p[3], &p[4], &p[5],
+                                    &p[6], &p[7], &p[8], &p[9], &p[10], &p[11], &p[12]);
+        if (got != 18) continue;
+        sgemm_config c = from_point(p);
+        if (violates(c) || M < 0 || N < 0 || K < 0 || layout < 0 || layout > 3) continue;
+        g_tuned[ShapeKey{M, N, K, layout}] = Tuned{c, ms};
+        ++added;
+    }
+    std::fclose(f);
+    return added;
+}
+
+void autoload_locked() {
+    if (g_tuned_autoloaded) return;
+    g_tuned_autoloaded = true;
+    if (const char *env = std::getenv("SGEMM_TUNED_CONFIGS")) {
+        load_cache_file_locked(env);
+        return;
+    }
+    const std::string p = library_dir() + "/../tuned_configs.txt";
+    load_cache_file_locked(p.c_str());
+}
+
+// Built-in fallback when nothing has been tuned: an MFMA variant sized to the problem.
+sgemm_config default_config(int M, int N, int K) {
+    (void)K;
+    sgemm_config c{};
+    c.kwg = 16; c.vwm = 4; c.vwn = 4; c.sa = 1; c.sb = 1; c.pad = 1; c.kwi = 8; c.mfma = 1; c.grp = 1;
+    const long long area = (long long)M * N;
+    if (area >= 2048ll * 2048ll) { c.mwg = 128; c.nwg = 128; c.mdimc = 16; c.ndimc = 16; }
+    else if (area >= 512ll * 512ll) { c.mwg = 64; c.nwg = 64; c.mdimc = 16; c.ndimc = 16; }
+    else { c.mwg = 32; c.nwg = 32; c.mdimc = 8; c.ndimc = 8; c.grp = 0; }
+    return c;
+}
+
+int select_config_locked(int M, int N, int K, int layout, sgemm_config *out) {
+    autoload_locked();
+    auto it = g_tuned.find(ShapeKey{M, N, K, layout});
+    if (it != g_tuned.end()) { *out = it->second.cfg; return SGEMM_OK; }
+    // nearest tuned shape of the same layout, by distance between the logarithms of the sizes
+    double best = -1.0;
+    for (auto &kv : g_tuned) {
+        if (std::get<3>(kv.first) != layout) continue;
+        const double dm = std::log2((double)std::max(M, 1)) - std::log2((double)std::max(std::get<0>(kv.first), 1));
+        const double dn = std::log2((double)std::max(N, 1)) - std::log2((double)std::max(std::get<1>(kv.first), 1));
+        const double dk = std::log2((double)std::max(K, 1)) - std::log2((double)std::max(std::get<2>(kv.first), 1));
+        const double d = dm * dm + dn * dn + dk * dk;
+        if (best < 0.0 || d < best) { best = d; *out = kv.second.cfg; }
+    }
+    if (best >= 0.0) return SGEMM_OK;
+    *out = default_config(M, N, K);
+    return SGEMM_OK;
+}
+
+int check_gemm_args(int M, int N, int K, const float *A, int lda, const float *B, int ldb,
+                    const float *C, int ldc, int layout, bool need_ab) {
+    if (M < 0 || N < 0 || K < 0) return SGEMM_E_BADARG;
+    if (layout < 0 || layout > 3) return SGEMM_E_BADARG;
+    if (M == 0 || N == 0) return SGEMM_OK;
+    if (!C || ldc < N) return SGEMM_E_BADARG;
+    if (need_ab && K > 0) {
+        if (!A || !B) return SGEMM_E_BADARG;
+        if (lda < ((layout & 1) ? M : K)) return SGEMM_E_BADARG;
+        if (ldb < ((layout & 2) ? K : N)) return SGEMM_E_BADARG;
+    }
+    return SGEMM_OK;
+}
+
+bool aligned_for(const void *p, int ld, int vw) {
+    return ((uintptr_t)p % (uintptr_t)(4 * vw)) == 0 && (ld % vw) == 0;
+}
+
+// The variant that will really be launched for this call.
+VariantKey resolve_variant(const sgemm_config &cfg, int M, int N, int K, const float *A, int lda,
+                           const float *B, int ldb, const float *C, int ldc, int layout) {
+    VariantKey key{cfg, layout, 0};
+    if (key.cfg.sa && key.cfg.vwm > 1 && !aligned_for(A, lda, key.cfg.vwm)) key.cfg.vwm = 1;
+    const bool vwn_loads_b = key.cfg.sb;
+    const bool vwn_stores_c = (key.cfg.mfma == 0);
+    if (key.cfg.vwn > 1 && ((vwn_loads_b && !aligned_for(B, ldb, key.cfg.vwn)) ||
+                            (vwn_stores_c && !aligned_for(C, ldc, key.cfg.vwn))))
+        key.cfg.vwn = 1;
+    key.edge = (M % cfg.mwg || N % cfg.nwg || K % cfg.kwg) ? 1 : 0;
+    return key;
+}
+
+int launch_loaded(hipStream_t s, const LoadedKernel &k, const sgemm_config &cfg, int M, int N, int K,
+                  float alpha, const float *A, int lda, const float *B, int ldb, float beta, float *C,
+                  int ldc) {
+    int tiles_m = (M + cfg.mwg - 1) / cfg.mwg;
+    int tiles_n = (N + cfg.nwg - 1) / cfg.nwg;
+    const long long wgs = (long long)tiles_m * tiles_n;
+    if (wgs > 0x7fffffffll) return SGEMM_E_BADARG;
+    void *args[] = {&M, &N, &K, &alpha, &A, &lda, &B, &ldb, &beta, &C, &ldc, &tiles_m, &tiles_n};
+    const hipError_t e = hipModuleLaunchKernel(k.fn, (unsigned)wgs, 1, 1, (unsigned)k.threads, 1, 1,
+                                               0, s, args, nullptr);
+    if (e != hipSuccess) {
+        set_error(std::string("hipModuleLaunchKernel: ") + hipGetErrorString(e));
+        return SGEMM_E_LAUNCH;
+    }
+    return SGEMM_OK;
+}
+
+int get_loaded(const VariantKey &key, std::shared_ptr<LoadedKernel> *out) {
+    const std::string name = key.macros();
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        auto it = g_loaded.find(name);
+        if (it != g_loaded.end()) { *out = it->second; return SGEMM_OK; }
+    }
+    std::string log;
+    std::shared_ptr<LoadedKernel> k;
+    const int rc = load_kernel(key, &k, &log);
+    if (rc != SGEMM_OK) {
+        set_error(log);
+        return rc;
+    }
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (g_loaded.size() >= kMaxLoaded) {
+        (void)hipDeviceSynchronize(); // no variant may still be running when its module goes away
+        g_loaded.clear();
+    }
+    g_loaded[name] = k;
+    *out = std::move(k);
+    return SGEMM_OK;
+}
+
+int run_config(hipStream_t s, const sgemm_config &cfg, int M, int N, int K, float alpha,
+               const float *A, int lda, const float *B, int ldb, float beta, float *C, int ldc,
+               int layout) {
+    const bool need_ab = (alpha != 0.0f);
+    int rc = check_gemm_args(M, N, K, A, lda, B, ldb, C, ldc, layout, need_ab);
+    if (rc != SGEMM_OK) return rc;
+    if (violates(cfg)) return SGEMM_E_INVALID;
+    if (M == 0 || N == 0) return SGEMM_OK;
+    if (K == 0 || alpha == 0.0f) {
+        if (beta == 1.0f) return SGEMM_OK;
+        return sgemm_util::launch_scale(s, M, N, beta, C, ldc) == hipSuccess ? SGEMM_OK : SGEMM_E_LAUNCH;
+    }
+    const VariantKey key = resolve_variant(cfg, M, N, K, A, lda, B, ldb, C, ldc, layout);
+    std::shared_ptr<LoadedKernel> k;
+    rc = get_loaded(key, &k);
+    if (rc != SGEMM_OK) return rc;
+    return launch_loaded(s, *k, key.cfg, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc);
+}
+
+StrategyParams params_from(const tune_opts *o) {
+    StrategyParams p;
+    if (!o) return p;
+    if (o->sa_T > 0) p.sa_T = o->sa_T;
+    p.sa_raw_ms = o->sa_raw_ms != 0;
+    if (o->pso_S > 0) p.pso_S = o->pso_S;
+    if (o->pso_alpha != 0 || o->pso_beta != 0 || o->pso_gamma != 0) {
+        p.pso_alpha = o->pso_alpha; p.pso_beta = o->pso_beta; p.pso_gamma = o->pso_gamma;
+    }
+    if (o->random_fraction > 0) p.random_fraction = o->random_fraction;
+    return p;
+}
+
+void fill_result(const Space &space, const SearchResult &r, double flops, tune_result *out) {
+    if (!out) return;
+    *out = tune_result{};
+    out->best_index = r.best_index;
+    out->evaluations = r.evaluations;
+    out->failed = r.failed;
+    out->space_size = (int)space.configs.size();
+    out->evals_to_best = r.evals_to_best;
+    if (r.best_index >= 0) {
+        out->best = from_point(space.configs[r.best_index]);
+        out->best_ms = (float)r.best_cost;
+        out->best_gflops = (float)(flops / (r.best_cost * 1e-3) * 1e-9);
+    }
+}
+
+struct DeviceBuffer {
+    void *p = nullptr;
+    ~DeviceBuffer() { if (p) (void)hipFree(p); }
+    hipError_t alloc(size_t bytes) { return hipMalloc(&p, bytes ? bytes : 4); }
+    float *f() const { return static_cast<float *>(p); }
+};
+
+struct Event {
+    hipEvent_t e = nullptr;
+    Event() { (void)hipEventCreate(&e); }
+    ~Event() { if (e) (void)hipEventDestroy(e); }
+};
+
+double median(std::vector<double> v) {
+    std::sort(v.begin(), v.end());
+    const size_t n = v.size();
+    return n % 2 ? v[n / 2] : 0.5 * (v[n / 2 - 1] + v[n / 2]);
+}
+
+} // namespace
+
+extern "C" {
+
+const char *sgemm_last_error(void) { return t_last_error.c_str(); }
+
+const char *sgemm_status_string(int status) {
+    switch (status) {
+    case SGEMM_OK: return "ok";
+    case SGEMM_E_BADARG: return "bad argument";
+    case SGEMM_E_NOCONFIG: return "no configuration";
+    case SGEMM_E_COMPILE: return "kernel compilation failed";
+    case SGEMM_E_LAUNCH: return "HIP call failed";
+    case SGEMM_E_VERIFY: return "verification against the reference kernel failed";
+    case SGEMM_E_INVALID: return "configuration violates a constraint";
+    case SGEMM_E_IO: return "cache file i/o failed";
+    case SGEMM_E_NODEVICE: return "no HIP device";
+    case SGEMM_E_RESOURCE: return "variant spills registers or exceeds LDS";
+    default: return status > 0 ? "count" : "unknown status";
+    }
+}
+
+int sgemm_set_stream(void *hip_stream) {
+    std::lock_guard<std::mutex> lock(g_mu);
+    g_stream = static_cast<hipStream_t>(hip_stream);
+    return SGEMM_OK;
+}
+
+int sgemm_run_config(void *hip_stream, const sgemm_config *cfg, int M, int N, int K, float alpha,
+                     const float *A, int lda, const float *B, int ldb, float beta, float *C, int ldc,
+                     int layout) {
+    if (!cfg) return SGEMM_E_BADARG;
+    return run_config(static_cast<hipStream_t>(hip_stream), *cfg, M, N, K, alpha, A, lda, B, ldb,
+                      beta, C, ldc, layout);
+}
+
+int sgemm_tuned_on(void *hip_stream, int M, int N, int K, float alpha, const float *A, int lda,
+                   const float *B, int ldb, float beta, float *C, int ldc, int layout) {
+    const int rc = check_gemm_args(M, N, K, A, lda, B, ldb, C, ldc, layout, alpha != 0.0f);
+    if (rc != SGEMM_OK) return rc;
+    sgemm_config cfg;
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        select_config_locked(M, N, K, layout, &cfg);
+    }
+    return run_config(static_cast<hipStream_t>(hip_stream), cfg, M, N, K, alpha, A, lda, B, ldb, beta,
+                      C, ldc, layout);
+}
+
+int sgemm_tuned(int M, int N, int K, float alpha, const float *A, int lda, const float *B, int ldb,
+                float beta, float *C, int ldc, int layout) {
+    hipStream_t s;
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        s = g_stream;
+    }
+    return sgemm_tuned_on(s, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, layout);
+}
+
+int sgemm_reference(void *hip_stream, int M, int N, int K, float alpha, const float *A, int lda,
+                    const float *B, int ldb, float beta, float *C, int ldc, int layout) {
+    const int rc = check_gemm_args(M, N, K, A, lda, B, ldb, C, ldc, layout, alpha != 0.0f);
+    if (rc != SGEMM_OK) return rc;
+    return sgemm_util::launch_reference(static_cast<hipStream_t>(hip_stream), M, N, K, alpha, A, lda, B,
+                                        ldb, beta, C, ldc, layout) == hipSuccess
+               ? SGEMM_OK
+               : SGEMM_E_LAUNCH;
+}
+
+/* ---- search space ------------------------------------------------------------------- */
+
+int sgemm_space_size(int space) {
+    const Space *s = get_space(space);
+    return s ? (int)s->configs.size() : SGEMM_E_BADARG;
+}
+
+long long sgemm_space_raw_size(int space) {
+    const Space *s = get_space(space);
+    return s ? s->raw : SGEMM_E_BADARG;
+}
+
+int sgemm_space_get(int space, int index, sgemm_config *out) {
+    const Space *s = get_space(space);
+    if (!s || !out || index < 0 || index >= (int)s->configs.size()) return SGEMM_E_BADARG;
+    *out = from_point(s->configs[index]);
+    return SGEMM_OK;
+}
+
+int sgemm_space_find(int space, const sgemm_config *cfg) {
+    const Space *s = get_space(space);
+    if (!s || !cfg) return SGEMM_E_BADARG;
+    const int i = s->find(to_point(*cfg));
+    return i >= 0 ? i : SGEMM_E_INVALID;
+}
+
+int sgemm_space_dims(int space) { return get_space(space) ? kDims : SGEMM_E_BADARG; }
+
+int sgemm_space_values(int space, int dim, int *values, int cap) {
+    const Space *s = get_space(space);
+    if (!s || dim < 0 || dim >= kDims) return SGEMM_E_BADARG;
+    const auto &v = s->values[dim];
+    for (int i = 0; i < (int)v.size() && i < cap && values; ++i) values[i] = v[i];
+    return (int)v.size();
+}
+
+int sgemm_config_check(const sgemm_config *cfg) {
+    if (!cfg) return SGEMM_E_BADARG;
+    return violates(*cfg) ? SGEMM_E_INVALID : SGEMM_OK;
+}
+
+int sgemm_config_lds_bytes(const sgemm_config *cfg) {
+    if (!cfg) return SGEMM_E_BADARG;
+    return lds_bytes(*cfg);
+}
+
+int sgemm_config_default(int M, int N, int K, int layout, sgemm_config *out) {
+    if (!out || M < 0 || N < 0 || K < 0 || layout < 0 || layout > 3) return SGEMM_E_BADARG;
+    *out = default_config(M, N, K);
+    return SGEMM_OK;
+}
+
+/* ---- kernel generator ---------------------------------------------------------------- */
+
+int sgemm_kernel_cache_dir(const char *path) {
+    if (!path || !*path) return SGEMM_E_BADARG;
+    set_cache_dir(path);
+    return SGEMM_OK;
+}
+
+int sgemm_kernel_compile(const sgemm_config *cfg, int layout, int edge, sgemm_kernel_info *info) {
+    if (!cfg || layout < 0 || layout > 3) return SGEMM_E_BADARG;
+    if (violates(*cfg)) return SGEMM_E_INVALID;
+    CodeObject co;
+    std::string log;
+    const int rc = get_code_object(VariantKey{*cfg, layout, edge ? 1 : 0}, &co, &log);
+    if (rc != SGEMM_OK) set_error(log);
+    if (info) *info = co.info;
+    return rc;
+}
+
+int sgemm_kernel_macros(const sgemm_config *cfg, int layout, int edge, char *buf, int cap) {
+    if (!cfg || !buf || cap <= 0) return SGEMM_E_BADARG;
+    const std::string m = VariantKey{*cfg, layout, edge ? 1 : 0}.macros();
+    if ((int)m.size() + 1 > cap) return SGEMM_E_BADARG;
+    std::memcpy(buf, m.c_str(), m.size() + 1);
+    return SGEMM_OK;
+}
+
+/* ---- per-shape cache ------------------------------------------------------------------ */
+
+int sgemm_config_get(int M, int N, int K, int layout, sgemm_config *out) {
+    if (!out) return SGEMM_E_BADARG;
+    std::lock_guard<std::mutex> lock(g_mu);
+    autoload_locked();
+    auto it = g_tuned.find(ShapeKey{M, N, K, layout});
+    if (it == g_tuned.end()) return SGEMM_E_NOCONFIG;
+    *out = it->second.cfg;
+    return SGEMM_OK;
+}
+
+int sgemm_config_set(int M, int N, int K, int layout, const sgemm_config *cfg, float ms) {
+    if (!cfg || M < 0 || N < 0 || K < 0 || layout < 0 || layout > 3) return SGEMM_E_BADARG;
+    if (violates(*cfg)) return SGEMM_E_INVALID;
+    std::lock_guard<std::mutex> lock(g_mu);
+    autoload_locked();
+    g_tuned[ShapeKey{M, N, K, layout}] = Tuned{*cfg, ms};
+    return SGEMM_OK;
+}
+
+int sgemm_config_select(int M, int N, int K, int layout, sgemm_config *out) {
+    if (!out || M < 0 || N < 0 || K < 0 || layout < 0 || layout > 3) return SGEMM_E_BADARG;
+    std::lock_guard<std::mutex> lock(g_mu);
+    return select_config_locked(M, N, K, layout, out);
+}
+
+int sgemm_cache_load(const char *path) {
+    if (!path) return SGEMM_E_BADARG;
+    std::lock_guard<std::mutex> lock(g_mu);
+    autoload_locked();
+    const int rc = load_cache_file_locked(path);
+    return rc < 0 ? rc : SGEMM_OK;
+}
+
+int sgemm_cache_save(const char *path) {
+    if (!path) return SGEMM_E_BADARG;
+    std::lock_guard<std::mutex> lock(g_mu);
+    autoload_locked();
+    FILE *f = std::fopen(path, "w");
+    if (!f) return SGEMM_E_IO;
+    std::fprintf(f, "# M N K layout ms MWG NWG KWG MDIMC NDIMC VWM VWN SA SB PAD KWI MFMA GRP\n");
+    for (auto &kv : g_tuned) {
+        const Point p = to_point(kv.second.cfg);
+        std::fprintf(f, "%d %d %d %d %.6g", std::get<0>(kv.first), std::get<1>(kv.first),
+                     std::get<2>(kv.first), std::get<3>(kv.first), kv.second.ms);
+        for (int v : p) std::fprintf(f, " %d", v);
+        std::fprintf(f, "\n");
+    }
+    return std::fclose(f) == 0 ? SGEMM_OK : SGEMM_E_IO;
+}
+
+int sgemm_cache_clear(void) {
+    std::lock_guard<std::mutex> lock(g_mu);
+    g_tuned_autoloaded = true; // an explicit clear also drops the auto-loaded entries
+    g_tuned.clear();
+    return SGEMM_OK;
+}
+
+int sgemm_cache_count(void) {
+    std::lock_guard<std::mutex> lock(g_mu);
+    autoload_locked();
+    return (int)g_tuned.size();
+}
+
+/* ---- device facts ---------------------------------------------------------------------- */
+
+int sgemm_device_peak(float *gflops, int *compute_units, int *clock_mhz) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return SGEMM_E_NODEVICE;
+    int cus = 0, khz = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        hipDeviceGetAttribute(&khz, hipDeviceAttributeClockRate, dev) != hipSuccess)
+        return SGEMM_E_NODEVICE;
+    if (compute_units) *compute_units = cus;
+    if (clock_mhz) *clock_mhz = khz / 1000;
+    // 4 SIMDs x (one 32x32x2 fp32 MFMA = 4096 FLOP per 64 cycles) = 256 FLOP per clock per CU
+    if (gflops) *gflops = (float)((double)cus * 256.0 * (double)khz * 1e-6);
+    return SGEMM_OK;
+}
+
+/* ---- tuning ------------------------------------------------------------------------------ */
+
+int tune_replay(int space_id, const float *ms_table, int table_len, int strategy, int budget,
+                unsigned long long seed, const tune_opts *opts, int *visited, int visited_cap,
+                tune_result *out) {
+    const Space *space = get_space(space_id);
+    if (!space || !ms_table) return SGEMM_E_BADARG;
+    if (strategy < 0 || strategy > 3) return SGEMM_E_BADARG;
+    const int n = (int)space->configs.size();
+    if (n == 0) return SGEMM_E_NOCONFIG;
+    if (table_len != n) return SGEMM_E_BADARG;
+    const SearchResult r = run_search(*space, strategy, budget, seed, params_from(opts),
+                                      [&](int i) { return (double)ms_table[i]; });
+    fill_result(*space, r, 0.0, out);
+    if (visited)
+        for (int i = 0; i < (int)r.visited.size() && i < visited_cap; ++i) visited[i] = r.visited[i];
+    return r.evaluations;
+}
+
+int tune_ex(int M, int N, int K, int layout, float alpha, float beta, int strategy, int budget,
+            unsigned long long seed, const tune_opts *opts, tune_result *out) {
+    if (M <= 0 || N <= 0 || K <= 0 || layout < 0 || layout > 3) return SGEMM_E_BADARG;
+    if (strategy < 0 || strategy > 3) return SGEMM_E_BADARG;
+    const Space *space = get_space(opts ? opts->space : SGEMM_SPACE_FULL);
+    if (!space) return SGEMM_E_BADARG;
+    if (space->configs.empty()) return SGEMM_E_NOCONFIG;
+    const int warmup = (opts && opts->warmup > 0) ? opts->warmup : 2;
+    const int reps = (opts && opts->reps > 0) ? opts->reps : 7;
+    const bool verify = !(opts && opts->verify_off);
+    const double cut = (opts && opts->cut_factor != 0.0f) ? opts->cut_factor : 3.0;
+
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) return SGEMM_E_NODEVICE;
+    hipStream_t s;
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        s = g_stream;
+    }
+    const auto wall0 = std::chrono::steady_clock::now();
+
+    // ---- operands: the caller's, or library-owned synthetic ones -------------------------
+    const int a_rows = (layout & 1) ? K : M, a_cols = (layout & 1) ? M : K;
+    const int b_rows = (layout & 2) ? N : K, b_cols = (layout & 2) ? K : N;
+    DeviceBuffer ownA, ownB, ownC, ownC0, ref, words;
+    const float *A, *B, *C0 = nullptr;
+    float *C;
+    int lda, ldb, ldc;
+    if (opts && opts->A) {
+        if (!opts->B || !opts->C) return SGEMM_E_BADARG;
+        A = opts->A; B = opts->B; C = opts->C; C0 = opts->C0;
+        lda = opts->lda; ldb = opts->ldb; ldc = opts->ldc;
+        if (lda < a_cols || ldb < b_cols || ldc < N) return SGEMM_E_BADARG;
+        if (beta != 0.0f && !C0) return SGEMM_E_BADARG;
+    } else {
+        lda = a_cols; ldb = b_cols; ldc = N;
+        if (ownA.alloc((size_t)a_rows * lda * 4) != hipSuccess || ownB.alloc((size_t)b_rows * ldb * 4) != hipSuccess ||
+            ownC.alloc((size_t)M * ldc * 4) != hipSuccess)
+            return SGEMM_E_LAUNCH;
+        (void)sgemm_util::launch_fill_uniform(s, ownA.f(), a_rows, a_cols, lda, seed * 3 + 1);
+        (void)sgemm_util::launch_fill_uniform(s, ownB.f(), b_rows, b_cols, ldb, seed * 3 + 2);
+        A = ownA.f(); B = ownB.f(); C = ownC.f();
+        if (beta != 0.0f) {
+            if (ownC0.alloc((size_t)M * ldc * 4) != hipSuccess) return SGEMM_E_LAUNCH;
+            (void)sgemm_util::launch_fill_uniform(s, ownC0.f(), M, N, ldc, seed * 3 + 3);
+            C0 = ownC0.f();
+        }
+    }
+    if (words.alloc(16) != hipSuccess) return SGEMM_E_LAUNCH;
+    unsigned int *dwords = static_cast<unsigned int *>(words.p);
+
+    // ---- reference result and tolerance, once per search ----------------------------------
+    float abs_tol = 0.0f;
+    const float rel_tol = 1e-6f;
+    if (verify) {
+        if (ref.alloc((size_t)M * N * 4) != hipSuccess) return SGEMM_E_LAUNCH;
+        if (beta != 0.0f) (void)sgemm_util::launch_copy2d(s, ref.f(), N, C0, ldc, M, N);
+        if (sgemm_util::launch_reference(s, M, N, K, alpha, A, lda, B, ldb, beta, ref.f(), N, layout) != hipSuccess)
+            return SGEMM_E_LAUNCH;
+        unsigned int bits[2] = {0, 0};
+        (void)sgemm_util::launch_absmax(s, A, a_rows, a_cols, lda, dwords);
+        (void)sgemm_util::launch_absmax(s, B, b_rows, b_cols, ldb, dwords + 1);
+        if (hipMemcpyAsync(bits, dwords, 8, hipMemcpyDeviceToHost, s) != hipSuccess ||
+            hipStreamSynchronize(s) != hipSuccess)
+            return SGEMM_E_LAUNCH;
+        float amax, bmax;
+        std::memcpy(&amax, &bits[0], 4);
+        std::memcpy(&bmax, &bits[1], 4);
+        abs_tol = 1e-5f * (float)K * amax * bmax;
+    }
+
+    FILE *logf = (opts && opts->log_path) ? std::fopen(opts->log_path, "a") : nullptr;
+    Event ev0, ev1;
+    double best_ms = 0.0; // best so far, for the early cut
+    double compile_ms_total = 0.0;
+    int hip_failure = 0;
+    const double flops = 2.0 * M * N * (double)K;
+
+    auto evaluate = [&](int idx) -> double {
+        const sgemm_config cfg = from_point(space->configs[idx]);
+        const char *status = "ok";
+        double ms = -1.0;
+        sgemm_kernel_info info{};
+        int samples = 0;
+        do {
+            if (hip_failure) { status = "skipped"; break; }
+            const VariantKey key = resolve_variant(cfg, M, N, K, A, lda, B, ldb, C, ldc, layout);
+            std::shared_ptr<LoadedKernel> k;
+            std::string log;
+            const int rc = load_kernel(key, &k, &log);
+            if (rc != SGEMM_OK) { status = rc == SGEMM_E_COMPILE ? "compile" : "load"; break; }
+            info = k->info;
+            compile_ms_total += info.compile_ms;
+            if (info.scratch_bytes > 0) { status = "spill"; break; }
+            if (info.lds_bytes > kLdsLimitBytes) { status = "lds"; break; }
+            auto launch = [&]() {
+                return launch_loaded(s, *k, key.cfg, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc);
+            };
+            // fresh C for the verified run, as every configuration gets fresh arguments
+            if (beta != 0.0f) (void)sgemm_util::launch_copy2d(s, C, ldc, C0, ldc, M, N);
+            (void)hipEventRecord(ev0.e, s);
+            if (launch() != SGEMM_OK) { status = "launch"; break; }
+            (void)hipEventRecord(ev1.e, s);
+            if (verify) (void)sgemm_util::launch_compare(s, C, ldc, ref.f(), N, M, N, abs_tol, rel_tol, dwords);
+            unsigned int bits[2] = {0, 0};
+            if (verify) (void)hipMemcpyAsync(bits, dwords, 8, hipMemcpyDeviceToHost, s);
+            if (hipStreamSynchronize(s) != hipSuccess) { status = "fault"; hip_failure = 1; break; }
+            if (verify && bits[0] != 0) { status = "verify"; break; }
+            float first = 0.0f;
+            (void)hipEventElapsedTime(&first, ev0.e, ev1.e);
+            for (int w = 1; w < warmup; ++w) launch();
+            // short kernels: several launches per sample so that a sample lasts >= 0.2 ms
+            int batch = 1;
+            if (first > 0.0f && first < 0.2f) batch = std::min(64, (int)std::ceil(0.2f / first));
+            std::vector<double> t;
+            bool failed = false;
+            for (int r = 0; r < reps; ++r) {
+                (void)hipEventRecord(ev0.e, s);
+                for (int b = 0; b < batch; ++b) launch();
+                (void)hipEventRecord(ev1.e, s);
+                if (hipEventSynchronize(ev1.e) != hipSuccess) { failed = true; break; }
+                float e = 0.0f;
+                (void)hipEventElapsedTime(&e, ev0.e, ev1.e);
+                t.push_back((double)e / batch);
+                if (r == 0 && cut > 0.0 && best_ms > 0.0 && t[0] > cut * best_ms) break;
+            }
+            if (failed || t.empty()) { status = "fault"; hip_failure = 1; break; }
+            samples = (int)t.size();
+            ms = median(t);
+            if (best_ms == 0.0 || ms < best_ms) best_ms = ms;
+        } while (false);
+        if (logf) {
+            const Point p = space->configs[idx];
+            std::fprintf(logf, "{\"M\":%d,\"N\":%d,\"K\":%d,\"layout\":%d,\"index\":%d,\"config\":[", M, N, K,
+                         layout, idx);
+            for (int d = 0; d < kDims; ++d) std::fprintf(logf, "%s%d", d ? "," : "", p[d]);
+            std::fprintf(logf, "],\"status\":\"%s\",\"ms\":%.6g,\"gflops\":%.6g,\"samples\":%d,\"vgprs\":%d,"
+                               "\"agprs\":%d,\"lds\":%d,\"scratch\":%d}\n",
+                         status, ms, ms > 0 ? flops / (ms * 1e-3) * 1e-9 : 0.0, samples, info.vgprs,
+                         info.agprs, info.lds_bytes, info.scratch_bytes);
+            std::fflush(logf);
+        }
+        return ms;
+    };
+
+    const SearchResult r = run_search(*space, strategy, budget, seed, params_from(opts), evaluate);
+    if (logf) std::fclose(logf);
+    (void)hipStreamSynchronize(s);
+    fill_result(*space, r, flops, out);
+    if (out) {
+        out->compile_ms = (float)compile_ms_total;
+        out->total_ms = std::chrono::duration<float, std::milli>(std::chrono::steady_clock::now() - wall0).count();
+    }
+    if (hip_failure) return SGEMM_E_LAUNCH;
+    if (r.best_index < 0) return SGEMM_E_NOCONFIG;
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        autoload_locked();
+        auto it = g_tuned.find(ShapeKey{M, N, K, layout});
+        if (it == g_tuned.end() || !(it->second.ms > 0) || r.best_cost < it->second.ms)
+            g_tuned[ShapeKey{M, N, K, layout}] = Tuned{from_point(space->configs[r.best_index]), (float)r.best_cost};
+    }
+    return r.evaluations;
+}
+
+int tune(int M, int N, int K, int strategy, int budget) {
+    return tune_ex(M, N, K, 0, 1.0f, 0.0f, strategy, budget, 0ull, nullptr, nullptr);
+}
+
+} // extern "C"

@@ -1,0 +1,171 @@
+#include "space.h"
+
+#include <mutex>
+
+namespace sgemm {
+
+static const char *kNames[kDims] = {"MWG", "NWG", "KWG", "MDIMC", "NDIMC", "VWM", "VWN",
+                                    "SA",  "SB",  "PAD", "KWI",   "MFMA",  "GRP"};
+
+const char *dim_name(int d) { return (d >= 0 && d < kDims) ? kNames[d] : "?"; }
+
+Point to_point(const sgemm_config &c) {
+    return Point{c.mwg, c.nwg, c.kwg, c.mdimc, c.ndimc, c.vwm, c.vwn,
+                 c.sa,  c.sb,  c.pad, c.kwi,   c.mfma,  c.grp};
+}
+
+sgemm_config from_point(const Point &p) {
+    sgemm_config c{};
+    c.mwg = p[0]; c.nwg = p[1]; c.kwg = p[2]; c.mdimc = p[3]; c.ndimc = p[4];
+    c.vwm = p[5]; c.vwn = p[6]; c.sa = p[7]; c.sb = p[8]; c.pad = p[9];
+    c.kwi = p[10]; c.mfma = p[11]; c.grp = p[12];
+    return c;
+}
+
+int lds_bytes(const sgemm_config &c, int layout) {
+    const int pad = c.pad ? 4 : 0;
+    int words = 0;
+    if (c.sa) words += (layout & 1) ? c.kwg * (c.mwg + pad) : c.mwg * (c.kwg + pad);
+    if (c.sb) words += (layout & 2) ? c.nwg * (c.kwg + pad) : c.kwg * (c.nwg + pad);
+    return 2 * 4 * words; // two buffers of floats
+}
+
+int lds_bytes(const sgemm_config &c) {
+    int worst = 0;
+    for (int layout = 0; layout < 4; ++layout) {
+        const int b = lds_bytes(c, layout);
+        if (b > worst) worst = b;
+    }
+    return worst;
+}
+
+static bool is_pow2_between(int v, int lo, int hi) { return v >= lo && v <= hi && (v & (v - 1)) == 0; }
+
+// Registers a lane needs at least: accumulators, one KWI block of operand fragments, the
+// global->LDS staging registers, and about 24 for addresses and loop state.
+int estimated_registers(const sgemm_config &c) {
+    const int nt = c.mdimc * c.ndimc;
+    const int mwi = c.mwg / c.mdimc, nwi = c.nwg / c.ndimc;
+    int regs = mwi * nwi + 24;
+    if (c.mfma) {
+        const int mt = c.mfma == 1 ? 32 : 16, mk = c.mfma == 1 ? 2 : 4;
+        regs += ((8 * mwi) / mt + (8 * nwi) / mt) * (c.kwi / mk);
+    } else {
+        regs += mwi + nwi;
+    }
+    if (c.sa) regs += c.mwg * c.kwg / nt;
+    if (c.sb) regs += c.nwg * c.kwg / nt;
+    return regs;
+}
+
+const char *violates(const sgemm_config &c) {
+    if (!is_pow2_between(c.mwg, 8, 512) || !is_pow2_between(c.nwg, 8, 512)) return "tile size";
+    if (!is_pow2_between(c.kwg, 2, 128)) return "KWG";
+    if (!is_pow2_between(c.mdimc, 1, 64) || !is_pow2_between(c.ndimc, 1, 64)) return "workgroup shape";
+    if (c.vwm != 1 && c.vwm != 2 && c.vwm != 4) return "VWM";
+    if (c.vwn != 1 && c.vwn != 2 && c.vwn != 4) return "VWN";
+    if ((c.sa | c.sb | c.pad | c.grp) & ~1) return "flag not 0/1";
+    if (c.mfma < 0 || c.mfma > 2) return "MFMA";
+    if (!is_pow2_between(c.kwi, 1, 32)) return "KWI";
+    if (c.reserved[0] || c.reserved[1] || c.reserved[2]) return "reserved field set";
+    const int nt = c.mdimc * c.ndimc;
+    // device limit: whole wavefronts, at most 1024 threads
+    if (nt % 64 != 0 || nt > kMaxThreads) return "threads per workgroup";
+    if (c.mwg % c.mdimc || c.nwg % c.ndimc) return "tile not divisible by workgroup shape";
+    const int mwi = c.mwg / c.mdimc, nwi = c.nwg / c.ndimc;
+    if (c.kwg % c.kwi) return "KWG not divisible by KWI";
+    if (c.sa) {
+        if (c.mwg % c.vwm || c.kwg % c.vwm) return "A tile row not divisible by VWM";
+        if ((c.mwg * c.kwg) % (nt * c.vwm)) return "A tile not divisible among threads";
+    } else if (c.vwm != 1) {
+        return "VWM without staging A"; // the width would change nothing: keep one spelling
+    }
+    if (c.sb) {
+        if (c.nwg % c.vwn || c.kwg % c.vwn) return "B tile row not divisible by VWN";
+        if ((c.nwg * c.kwg) % (nt * c.vwn)) return "B tile not divisible among threads";
+    }
+    if (!c.sa && !c.sb && c.pad) return "PAD without LDS";
+    if (c.mfma == 0) {
+        if (nwi % c.vwn) return "NWI not divisible by VWN";
+        if (mwi * nwi > 64) return "register tile too large";
+    } else {
+        if (c.mdimc % 8 || c.ndimc % 8) return "workgroup shape not made of 8x8 wave patches";
+        if (!c.sb && c.vwn != 1) return "VWN without staging B";
+        const int mt = c.mfma == 1 ? 32 : 16, mk = c.mfma == 1 ? 2 : 4;
+        if ((8 * mwi) % mt || (8 * nwi) % mt) return "wave tile not a multiple of the MFMA tile";
+        if (c.kwi % mk) return "KWI not a multiple of the MFMA depth";
+        if (mwi * nwi > 256) return "accumulator tile too large";
+    }
+    // device limits: 512 registers per lane (VGPR + AGPR), 160 KiB LDS per workgroup
+    if (estimated_registers(c) > (c.mfma ? 512 : 256)) return "register budget";
+    if (lds_bytes(c) > kLdsLimitBytes) return "LDS capacity";
+    return nullptr;
+}
+
+uint64_t Space::key(const Point &p) {
+    uint64_t h = 1469598103934665603ull;
+    for (int v : p) { h ^= (uint64_t)(uint32_t)v; h *= 1099511628211ull; }
+    return h;
+}
+
+int Space::find(const Point &p) const {
+    auto it = index.find(key(p));
+    if (it == index.end()) return -1;
+    return configs[it->second] == p ? it->second : -1;
+}
+
+static Space build(int preset) {
+    Space s;
+    s.preset = preset;
+    switch (preset) {
+    case SGEMM_SPACE_SMALL:
+        // MWG, NWG in {32,64}; KWG in {8,16}; staging on/off for both operands together
+        s.values = {{32, 64}, {32, 64}, {8, 16}, {8}, {8}, {1}, {1}, {0, 1}, {0, 1}, {0}, {2}, {0}, {0}};
+        break;
+    case SGEMM_SPACE_FULL:
+        s.values = {{32, 64, 128, 256}, {32, 64, 128, 256}, {8, 16, 32}, {8, 16}, {8, 16},
+                    {1, 4}, {1, 4}, {0, 1}, {0, 1}, {0, 1}, {2, 8}, {0, 1}, {0, 1}};
+        break;
+    case SGEMM_SPACE_MFMA:
+        s.values = {{64, 128, 256}, {64, 128, 256}, {8, 16, 32}, {8, 16, 32}, {8, 16, 32},
+                    {1, 2, 4}, {1, 2, 4}, {1}, {1}, {0, 1}, {2, 8}, {1, 2}, {0, 1}};
+        break;
+    default:
+        s.preset = -1;
+        return s;
+    }
+    s.raw = 1;
+    for (auto &v : s.values) s.raw *= (long long)v.size();
+    Point p{};
+    std::array<size_t, kDims> it{};
+    bool done = false;
+    while (!done) {
+        for (int d = 0; d < kDims; ++d) p[d] = s.values[d][it[d]];
+        sgemm_config c = from_point(p);
+        bool ok = violates(c) == nullptr;
+        if (preset == SGEMM_SPACE_SMALL && c.sa != c.sb) ok = false; // one LDS switch
+        if (ok) {
+            s.index.emplace(Space::key(p), (int)s.configs.size());
+            s.configs.push_back(p);
+        }
+        int d = kDims - 1; // odometer, last dimension fastest => lexicographic order
+        while (d >= 0 && ++it[d] == s.values[d].size()) { it[d] = 0; --d; }
+        if (d < 0) done = true;
+    }
+    return s;
+}
+
+const Space *get_space(int preset) {
+    static std::mutex mu;
+    static std::unordered_map<int, Space *> built;
+    std::lock_guard<std::mutex> lock(mu);
+    auto it = built.find(preset);
+    if (it != built.end()) return it->second;
+    Space s = build(preset);
+    if (s.preset < 0) return nullptr;
+    Space *keep = new Space(std::move(s));
+    built.emplace(preset, keep);
+    return keep;
+}
+
+} // namespace sgemm

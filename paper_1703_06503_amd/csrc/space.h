@@ -1,0 +1,48 @@
+// The tuning-parameter space of the SGEMM kernel family: value lists per parameter, the
+// constraints that prune their cartesian product, and the enumerated valid configurations.
+// (Paper: "Advanced usage" for constraints and device limits; "Tuning parameters" of the
+// matrix-multiplication case study for the parameters themselves.)
+#pragma once
+#include <array>
+#include <cstdint>
+#include <string>
+#include <unordered_map>
+#include <vector>
+
+#include "../../include/sgemm_tuned.h"
+
+namespace sgemm {
+
+constexpr int kDims = 13;              // tuned fields of sgemm_config, in field order
+constexpr int kLdsLimitBytes = 163840; // LDS per workgroup on gfx950
+constexpr int kMaxThreads = 1024;
+
+using Point = std::array<int, kDims>;
+
+Point to_point(const sgemm_config &c);
+sgemm_config from_point(const Point &p);
+const char *dim_name(int d);
+
+// Derived quantities of one configuration.
+int lds_bytes(const sgemm_config &c);       // worst case over the four storage layouts
+int lds_bytes(const sgemm_config &c, int layout);
+int estimated_registers(const sgemm_config &c);
+
+// nullptr if c satisfies every constraint, else a short reason.
+const char *violates(const sgemm_config &c);
+
+struct Space {
+    int preset = -1;
+    std::vector<std::vector<int>> values; // per dimension
+    std::vector<Point> configs;           // valid points, lexicographic in dimension order
+    std::unordered_map<uint64_t, int> index;
+    long long raw = 0;
+
+    int find(const Point &p) const;
+    static uint64_t key(const Point &p);
+};
+
+// Built once per preset and kept; nullptr for an unknown preset.
+const Space *get_space(int preset);
+
+} // namespace sgemm

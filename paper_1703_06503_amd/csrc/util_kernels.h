@@ -1,0 +1,23 @@
+// Host-callable launchers of the harness's fixed kernels (util_kernels.hip).
+#pragma once
+#include <hip/hip_runtime_api.h>
+
+namespace sgemm_util {
+
+hipError_t launch_reference(hipStream_t s, int M, int N, int K, float alpha, const float *A,
+                            int lda, const float *B, int ldb, float beta, float *C, int ldc,
+                            int layout);
+hipError_t launch_scale(hipStream_t s, int M, int N, float beta, float *C, int ldc);
+hipError_t launch_fill_uniform(hipStream_t s, float *dst, int rows, int cols, int ld,
+                               unsigned long long seed);
+// *out_bits (device) receives the bit pattern of max |x|.
+hipError_t launch_absmax(hipStream_t s, const float *src, int rows, int cols, int ld,
+                         unsigned int *out_bits);
+// two_words (device): [0] = number of elements outside abs_tol + rel_tol*|ref|,
+// [1] = bit pattern of the largest err / bound.
+hipError_t launch_compare(hipStream_t s, const float *got, int ldg, const float *ref, int ldr,
+                          int M, int N, float abs_tol, float rel_tol, unsigned int *two_words);
+hipError_t launch_copy2d(hipStream_t s, float *dst, int ldd, const float *src, int lds_, int rows,
+                         int cols);
+
+} // namespace sgemm_util

@@ -1,0 +1,189 @@
+// Small fixed kernels of the tuning harness (compiled ahead of time for gfx950): the
+// reference GEMM that every tuned variant is verified against, operand fill, the tolerance
+// check, |x| maximum, and the C = beta*C scaling used when alpha == 0 or K == 0.
+#include <hip/hip_runtime.h>
+
+#include "util_kernels.h"
+
+namespace {
+
+// One thread per element of C; products and sums in double in increasing k.  This is the
+// "reference kernel" of the paper's result verification (section "Advanced usage").
+__global__ void reference_kernel(int M, int N, int K, float alpha, const float *__restrict__ A,
+                                 int lda, const float *__restrict__ B, int ldb, float beta,
+                                 float *__restrict__ C, int ldc, int layout) {
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    const int i = blockIdx.y * blockDim.y + threadIdx.y;
+    if (i >= M || j >= N) return;
+    double sum = 0.0;
+    if (alpha != 0.0f) {
+        for (int k = 0; k < K; ++k) {
+            const float a = (layout & 1) ? A[(size_t)k * lda + i] : A[(size_t)i * lda + k];
+            const float b = (layout & 2) ? B[(size_t)j * ldb + k] : B[(size_t)k * ldb + j];
+            sum += (double)a * (double)b;
+        }
+    }
+    double r = (double)alpha * sum;
+    float *p = C + (size_t)i * ldc + j;
+    if (beta != 0.0f) r += (double)beta * (double)*p;
+    *p = (float)r;
+}
+
+__global__ void scale_kernel(int M, int N, float beta, float *__restrict__ C, int ldc) {
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    const int i = blockIdx.y * blockDim.y + threadIdx.y;
+    if (i >= M || j >= N) return;
+    float *p = C + (size_t)i * ldc + j;
+    *p = (beta == 0.0f) ? 0.0f : beta * *p;
+}
+
+__device__ inline unsigned long long mix64(unsigned long long z) {
+    z += 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+// rows x cols matrix with leading dimension ld, i.i.d. uniform on [-1, 1): a function of
+// (seed, row, col) only, so the values do not depend on ld or on the launch shape.
+__global__ void fill_uniform_kernel(float *__restrict__ dst, int rows, int cols, int ld,
+                                    unsigned long long seed) {
+    const size_t n = (size_t)rows * cols;
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < n;
+         e += (size_t)gridDim.x * blockDim.x) {
+        const size_t r = e / cols, c = e % cols;
+        const unsigned long long u = mix64(seed ^ mix64(e));
+        dst[r * ld + c] = (float)((double)(u >> 11) * (2.0 / 9007199254740992.0) - 1.0);
+    }
+}
+
+// out[0] = max |x| over a rows x cols matrix, as float bits (non-negative floats order like
+// their bit patterns).  *out must be zeroed by the caller.
+__global__ void absmax_kernel(const float *__restrict__ src, int rows, int cols, int ld,
+                              unsigned int *out) {
+    const size_t n = (size_t)rows * cols;
+    float m = 0.0f;
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < n;
+         e += (size_t)gridDim.x * blockDim.x) {
+        const float v = fabsf(src[(e / cols) * ld + e % cols]);
+        if (v > m || v != v) m = (v != v) ? __uint_as_float(0x7f800000u) : v;
+    }
+    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    if ((threadIdx.x & 63) == 0) atomicMax(out, __float_as_uint(m));
+}
+
+// Counts elements with |got - ref| > abs_tol + rel_tol*|ref| (NaN in exactly one of the two
+// counts as a violation) and keeps the largest excess ratio err / bound.
+__global__ void compare_kernel(const float *__restrict__ got, int ldg,
+                               const float *__restrict__ ref, int ldr, int M, int N,
+                               float abs_tol, float rel_tol, unsigned int *violations,
+                               unsigned int *worst_ratio_bits) {
+    const size_t n = (size_t)M * N;
+    unsigned int bad = 0;
+    float worst = 0.0f;
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < n;
+         e += (size_t)gridDim.x * blockDim.x) {
+        const float g = got[(e / N) * ldg + e % N];
+        const float r = ref[(e / N) * ldr + e % N];
+        const bool gn = (g != g), rn = (r != r);
+        if (gn || rn) {
+            if (gn != rn) { ++bad; worst = __uint_as_float(0x7f800000u); }
+            continue;
+        }
+        if (g == r) continue; // also covers equal infinities
+        const float bound = abs_tol + rel_tol * fabsf(r);
+        const float err = fabsf(g - r);
+        if (!(err <= bound)) ++bad;
+        const float ratio = bound > 0.0f ? err / bound : __uint_as_float(0x7f800000u);
+        if (ratio > worst) worst = ratio;
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+        bad += __shfl_xor(bad, o);
+        worst = fmaxf(worst, __shfl_xor(worst, o));
+    }
+    if ((threadIdx.x & 63) == 0) {
+        if (bad) atomicAdd(violations, bad);
+        atomicMax(worst_ratio_bits, __float_as_uint(worst));
+    }
+}
+
+__global__ void copy2d_kernel(float *__restrict__ dst, int ldd, const float *__restrict__ src,
+                              int lds_, int rows, int cols) {
+    const size_t n = (size_t)rows * cols;
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < n;
+         e += (size_t)gridDim.x * blockDim.x)
+        dst[(e / cols) * ldd + e % cols] = src[(e / cols) * lds_ + e % cols];
+}
+
+__global__ void zero_u32_kernel(unsigned int *p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
+inline int grid_for(size_t n, int block) {
+    size_t g = (n + block - 1) / block;
+    if (g > 256 * 16) g = 256 * 16;
+    if (g < 1) g = 1;
+    return (int)g;
+}
+
+} // namespace
+
+namespace sgemm_util {
+
+hipError_t launch_reference(hipStream_t s, int M, int N, int K, float alpha, const float *A,
+                            int lda, const float *B, int ldb, float beta, float *C, int ldc,
+                            int layout) {
+    if (M == 0 || N == 0) return hipSuccess;
+    dim3 block(64, 4), grid((N + 63) / 64, (M + 3) / 4);
+    hipLaunchKernelGGL(reference_kernel, grid, block, 0, s, M, N, K, alpha, A, lda, B, ldb, beta,
+                       C, ldc, layout);
+    return hipGetLastError();
+}
+
+hipError_t launch_scale(hipStream_t s, int M, int N, float beta, float *C, int ldc) {
+    if (M == 0 || N == 0) return hipSuccess;
+    dim3 block(64, 4), grid((N + 63) / 64, (M + 3) / 4);
+    hipLaunchKernelGGL(scale_kernel, grid, block, 0, s, M, N, beta, C, ldc);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_uniform(hipStream_t s, float *dst, int rows, int cols, int ld,
+                               unsigned long long seed) {
+    const size_t n = (size_t)rows * cols;
+    if (n == 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_uniform_kernel, dim3(grid_for(n, 256)), dim3(256), 0, s, dst, rows,
+                       cols, ld, seed);
+    return hipGetLastError();
+}
+
+hipError_t launch_absmax(hipStream_t s, const float *src, int rows, int cols, int ld,
+                         unsigned int *out_bits) {
+    hipLaunchKernelGGL(zero_u32_kernel, dim3(1), dim3(64), 0, s, out_bits, 1);
+    const size_t n = (size_t)rows * cols;
+    if (n == 0) return hipGetLastError();
+    hipLaunchKernelGGL(absmax_kernel, dim3(grid_for(n, 256)), dim3(256), 0, s, src, rows, cols, ld,
+                       out_bits);
+    return hipGetLastError();
+}
+
+hipError_t launch_compare(hipStream_t s, const float *got, int ldg, const float *ref, int ldr,
+                          int M, int N, float abs_tol, float rel_tol, unsigned int *two_words) {
+    hipLaunchKernelGGL(zero_u32_kernel, dim3(1), dim3(64), 0, s, two_words, 2);
+    const size_t n = (size_t)M * N;
+    if (n == 0) return hipGetLastError();
+    hipLaunchKernelGGL(compare_kernel, dim3(grid_for(n, 256)), dim3(256), 0, s, got, ldg, ref, ldr,
+                       M, N, abs_tol, rel_tol, two_words, two_words + 1);
+    return hipGetLastError();
+}
+
+hipError_t launch_copy2d(hipStream_t s, float *dst, int ldd, const float *src, int lds_, int rows,
+                         int cols) {
+    const size_t n = (size_t)rows * cols;
+    if (n == 0) return hipSuccess;
+    hipLaunchKernelGGL(copy2d_kernel, dim3(grid_for(n, 256)), dim3(256), 0, s, dst, ldd, src, lds_,
+                       rows, cols);
+    return hipGetLastError();
+}
+
+} // namespace sgemm_util

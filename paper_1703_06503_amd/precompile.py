@@ -1,0 +1,64 @@
+"""Fill the on-disk code-object cache ahead of time, in parallel, without a GPU:
+
+    python -m paper_1703_06503_amd.precompile --space 0 --layouts 0 --edge 0 --jobs 8
+
+Recompilation can dominate tuning time (paper, section "Search strategies and search-space
+properties"); compiling every variant of a space once, off-line, takes it out of the search."""
+import argparse
+import multiprocessing as mp
+import sys
+import time
+
+
+def _work(args):
+    space, layout, edge, lo, hi, step = args
+    from . import binding as b
+    n_new = n_fail = 0
+    for i in range(lo, hi, step):
+        cfg = b.sgemm_space_get(space, i)
+        try:
+            info = b.sgemm_kernel_compile(cfg, layout, edge)
+            n_new += 0 if info.from_cache else 1
+        except b.SgemmError:
+            n_fail += 1
+    return n_new, n_fail
+
+
+def precompile(space=0, layouts=(0,), edges=(0,), jobs=8, indices=None, verbose=True):
+    from . import binding as b
+    n = b.sgemm_space_size(space)
+    t0 = time.time()
+    total_new = total_fail = 0
+    ctx = mp.get_context("spawn")
+    with ctx.Pool(jobs) as pool:
+        for layout in layouts:
+            for edge in edges:
+                if indices is None:
+                    tasks = [(space, layout, edge, j, n, jobs * 8) for j in range(jobs * 8)]
+                    res = pool.map(_work, tasks)
+                else:
+                    tasks = [(space, layout, edge, i, i + 1, 1) for i in indices]
+                    res = pool.map(_work, tasks, chunksize=max(1, len(tasks) // (jobs * 4)))
+                total_new += sum(r[0] for r in res)
+                total_fail += sum(r[1] for r in res)
+                if verbose:
+                    print(f"space {space} layout {layout} edge {edge}: compiled so far "
+                          f"{total_new}, failed {total_fail}, {time.time() - t0:.0f} s", flush=True)
+    return total_new, total_fail
+
+
+def main(argv=None):
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--space", type=int, default=0)
+    ap.add_argument("--layouts", default="0")
+    ap.add_argument("--edge", default="0")
+    ap.add_argument("--jobs", type=int, default=8)
+    a = ap.parse_args(argv)
+    new, fail = precompile(a.space, [int(x) for x in a.layouts.split(",")],
+                           [int(x) for x in a.edge.split(",")], a.jobs)
+    print(f"compiled {new} variants, {fail} failed")
+    return 1 if fail else 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

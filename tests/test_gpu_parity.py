@@ -1,0 +1,255 @@
+"""GPU parity: every tested variant of the kernel family, driven through the C ABI, against
+the CPU oracle, element by element.  Sizes span several workgroup tiles and ragged tails."""
+import numpy as np
+import pytest
+
+from oracle import sgemm_oracle as orc
+from paper_1703_06503_amd import binding as b
+from paper_1703_06503_amd import synth
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+# The fixed sample of the full space that the parity tests walk (also what
+# `tests/precompile_test_variants.py` puts into the kernel cache ahead of time).
+FULL_SAMPLE = dict(space=b.SPACE_FULL, count=160, seed=1234)
+MFMA_SAMPLE = dict(space=b.SPACE_MFMA, count=80, seed=4321)
+EXACT_SHAPE = (256, 512, 96)      # multiples of every tile size: unguarded variants
+RAGGED_SHAPE = (200, 136, 68)     # guarded variants, several tiles for small configs
+RAGGED_BIG = (300, 520, 44)       # more than one tile even at 256 x 256
+
+
+def _sweep(space, indices, shape, alpha, beta, layout, seed, dist="uniform"):
+    M, N, K = shape
+    A, B, C = synth.make_inputs(M, N, K, layout, seed, dist)
+    ref = orc.sgemm(alpha, A, B, beta, C, layout)
+    worst = 0.0
+    for i in indices:
+        cfg = b.sgemm_space_get(space, i)
+        print(f"case space={space} index={i} {cfg} shape={shape} layout={layout}", flush=True)
+        got = gu.run_gpu(cfg, A, B, C, alpha, beta, layout)
+        worst = max(worst, gu.check_against_oracle(got, A, B, C, alpha, beta, layout, ref,
+                                                   what=f"space {space} index {i} {cfg}"))
+    return worst
+
+
+def test_small_space_all_16_configs_at_256_cubed():
+    """Benchmark configuration 1: 256^3, alpha=1, beta=0, uniform[-1,1] seed 0."""
+    w = synth.WORKLOADS["cfg1_256"]
+    assert b.sgemm_space_size(b.SPACE_SMALL) == 16
+    worst = _sweep(b.SPACE_SMALL, range(16), (w.M, w.N, w.K), w.alpha, w.beta, w.layout, w.seed)
+    assert worst <= 1.0
+
+
+def test_full_space_sample_exact_tiles():
+    _sweep(b.SPACE_FULL, gu.sample_configs(**FULL_SAMPLE), EXACT_SHAPE, 2.0, 0.5, 0, seed=21)
+
+
+def test_full_space_sample_ragged():
+    _sweep(b.SPACE_FULL, gu.sample_configs(**FULL_SAMPLE), RAGGED_SHAPE, 1.0, 1.0, 0, seed=22)
+
+
+def test_mfma_space_sample_exact_tiles():
+    _sweep(b.SPACE_MFMA, gu.sample_configs(**MFMA_SAMPLE), EXACT_SHAPE, 1.0, 0.0, 0, seed=23,
+           dist="normal")
+
+
+def test_mfma_space_sample_ragged():
+    _sweep(b.SPACE_MFMA, gu.sample_configs(**MFMA_SAMPLE), RAGGED_BIG, -1.5, 0.25, 0, seed=24)
+
+
+@pytest.mark.parametrize("layout", [1, 2, 3])
+def test_transposed_storage(layout):
+    idx = gu.sample_configs(b.SPACE_FULL, 40, seed=100 + layout)
+    _sweep(b.SPACE_FULL, idx, EXACT_SHAPE, 1.0, 0.0, layout, seed=30 + layout)
+    _sweep(b.SPACE_FULL, idx, RAGGED_SHAPE, 0.5, 2.0, layout, seed=40 + layout)
+
+
+def _some_configs():
+    """A vector-ALU variant, a 32x32x2 MFMA variant and a 16x16x4 MFMA variant."""
+    return [
+        b.make_config(64, 64, 16, 8, 8, 4, 4, 1, 1, 1, 8, 0, 0),
+        b.make_config(128, 128, 16, 16, 16, 4, 4, 1, 1, 1, 8, 1, 1),
+        b.make_config(64, 64, 16, 16, 16, 2, 2, 1, 1, 0, 8, 2, 1),
+    ]
+
+
+@pytest.mark.parametrize("which", [0, 1, 2])
+def test_integer_inputs_are_bit_exact(which):
+    """Small-integer operands: every summation order gives the same float, so the GPU must
+    equal the oracle exactly, whatever the tiling or MFMA blocking."""
+    cfg = _some_configs()[which]
+    assert b.sgemm_config_check(cfg) == 0
+    for shape in [(256, 256, 64), (130, 70, 33), (1, 1, 1), (5, 300, 2)]:
+        M, N, K = shape
+        A, B, C = synth.make_inputs(M, N, K, 0, seed=50, dist="smallint")
+        got = gu.run_gpu(cfg, A, B, C, 2.0, -3.0)
+        assert np.array_equal(got.astype(np.float64), orc.sgemm(2.0, A, B, -3.0, C)), shape
+
+
+@pytest.mark.parametrize("which", [0, 1, 2])
+def test_permutation_matrix_is_bit_exact(which):
+    cfg = _some_configs()[which]
+    rng = np.random.default_rng(51)
+    m, n = 192, 160
+    perm = rng.permutation(m)
+    P = np.zeros((m, m), dtype=np.float32)
+    P[np.arange(m), perm] = 1.0
+    B = rng.standard_normal((m, n)).astype(np.float32)
+    got = gu.run_gpu(cfg, P, B, np.zeros((m, n), np.float32), 1.0, 0.0)
+    assert np.array_equal(got, B[perm])
+
+
+@pytest.mark.parametrize("which", [0, 1, 2])
+def test_alpha_beta_edge_cases(which):
+    cfg = _some_configs()[which]
+    A, B, C = synth.make_inputs(150, 140, 60, 0, seed=52)
+    Cn = C.copy()
+    Cn[3, 5] = np.nan
+    Cn[149, 139] = np.inf
+    # beta == 0: NaN/Inf in C must not reach the result
+    got = gu.run_gpu(cfg, A, B, Cn, 1.0, 0.0)
+    assert np.all(np.isfinite(got))
+    gu.check_against_oracle(got, A, B, Cn, 1.0, 0.0)
+    # alpha == 0: A and B are not read (NaN there is harmless); C = beta*C exactly
+    An = A.copy()
+    An[0, 0] = np.nan
+    got = gu.run_gpu(cfg, An, B, C, 0.0, 1.0)
+    assert np.array_equal(got, C)
+    got = gu.run_gpu(cfg, An, B, Cn, 0.0, 0.0)
+    assert np.array_equal(got, np.zeros_like(C))
+    got = gu.run_gpu(cfg, A, B, C, 0.0, 0.5)
+    assert np.array_equal(got, (0.5 * C).astype(np.float32))
+    # beta != 0 reads C: NaN and Inf land exactly where they were
+    got = gu.run_gpu(cfg, A, B, Cn, 1.0, 1.0)
+    assert np.isnan(got[3, 5]) and np.isinf(got[149, 139])
+    assert np.isfinite(got).sum() == got.size - 2
+    # (1, -1) with C_in = A B: residual within the bound around zero
+    AB = orc.sgemm(1.0, A, B, 0.0, None).astype(np.float32)
+    got = gu.run_gpu(cfg, A, B, AB, 1.0, -1.0)
+    gu.check_against_oracle(got, A, B, AB, 1.0, -1.0)
+
+
+@pytest.mark.parametrize("which", [0, 1, 2])
+def test_leading_dimensions_and_untouched_padding(which):
+    """ld > row length, unaligned for vector access; elements of C outside M x N stay
+    bit-identical, including guard rows after the matrix."""
+    import torch
+    cfg = _some_configs()[which]
+    M, N, K, lda, ldb, ldc = 97, 83, 45, 51, 90, 89
+    rng = np.random.default_rng(53)
+    Abuf = rng.uniform(-1, 1, (M, lda)).astype(np.float32)
+    Bbuf = rng.uniform(-1, 1, (K, ldb)).astype(np.float32)
+    Cbuf = rng.uniform(-1, 1, (M + 3, ldc)).astype(np.float32)   # 3 guard rows
+    dA, dB, dC = (torch.from_numpy(x).cuda() for x in (Abuf, Bbuf, Cbuf.copy()))
+    b.sgemm_run_config(None, cfg, M, N, K, 1.25, dA, lda, dB, ldb, 0.5, dC, ldc, 0)
+    torch.cuda.synchronize()
+    out = dC.cpu().numpy()
+    assert np.array_equal(out[:M, N:], Cbuf[:M, N:]) and np.array_equal(out[M:], Cbuf[M:])
+    A, B, C = Abuf[:, :K].copy(), Bbuf[:, :N].copy(), Cbuf[:M, :N].copy()
+    gu.check_against_oracle(out[:M, :N], A, B, C, 1.25, 0.5)
+
+
+def test_degenerate_sizes():
+    import torch
+    cfg = _some_configs()[1]
+    dA = torch.zeros(16, device="cuda"); dB = torch.zeros(16, device="cuda")
+    dC = torch.full((4, 4), 7.0, device="cuda")
+    # M == 0 or N == 0: no-op; K == 0: C = beta*C
+    b.sgemm_run_config(None, cfg, 0, 4, 4, 1.0, dA, 4, dB, 4, 0.0, dC, 4, 0)
+    b.sgemm_run_config(None, cfg, 4, 0, 4, 1.0, dA, 4, dB, 4, 0.0, dC, 4, 0)
+    torch.cuda.synchronize()
+    assert torch.all(dC == 7.0)
+    b.sgemm_run_config(None, cfg, 4, 4, 0, 1.0, dA, 4, dB, 4, 0.5, dC, 4, 0)
+    torch.cuda.synchronize()
+    assert torch.all(dC == 3.5)
+    # bad arguments are errors, not launches
+    for args in [(-1, 4, 4, 4, 4, 4), (4, 4, 4, 3, 4, 4), (4, 4, 4, 4, 3, 4), (4, 4, 4, 4, 4, 3)]:
+        M, N, K, lda, ldb, ldc = args
+        with pytest.raises(b.SgemmError) as e:
+            b.sgemm_run_config(None, cfg, M, N, K, 1.0, dA, lda, dB, ldb, 0.0, dC, ldc, 0)
+        assert e.value.status == b.E_BADARG
+    with pytest.raises(b.SgemmError):
+        b.sgemm_run_config(None, cfg, 4, 4, 4, 1.0, dA, 4, dB, 4, 0.0, dC, 4, 7)
+    bad = b.make_config(100, 64, 16, 8, 8, 1, 1, 1, 1, 0, 2, 0, 0)
+    with pytest.raises(b.SgemmError) as e:
+        b.sgemm_run_config(None, bad, 4, 4, 4, 1.0, dA, 4, dB, 4, 0.0, dC, 4, 0)
+    assert e.value.status == b.E_INVALID
+
+
+def test_reference_kernel_against_oracle():
+    """The device reference kernel that tune() verifies against is itself held to the oracle."""
+    for layout in range(4):
+        A, B, C = synth.make_inputs(77, 131, 200, layout, seed=60 + layout)
+        got = gu.run_gpu(None, A, B, C, 1.5, -0.5, layout, entry="reference")
+        ref = orc.sgemm(1.5, A, B, -0.5, C, layout)
+        assert np.max(np.abs(got - ref)) <= 2.0 ** -23 * np.max(np.abs(ref))
+
+
+def test_run_to_run_determinism():
+    cfg = _some_configs()[1]
+    A, B, C = synth.make_inputs(384, 256, 512, 0, seed=61)
+    first = gu.run_gpu(cfg, A, B, C, 1.0, 0.0)
+    for _ in range(3):
+        assert np.array_equal(gu.run_gpu(cfg, A, B, C, 1.0, 0.0), first)
+
+
+# ---- full benchmark sizes: sampled outputs ------------------------------------------------
+# At 4096^3 the oracle cannot produce the whole matrix in test time, but every element is an
+# independent dot product: whole rows, whole columns, edge tiles and scattered elements are
+# computed one by one and compared under the same bound.
+
+def _sampled_check(workload, cfg, entry="config", rows=64, cols=64, scattered=4096):
+    import torch
+    w = synth.WORKLOADS[workload]
+    A, B, C = synth.make_workload(w)
+    dA, dB, dC = (torch.from_numpy(x).cuda() for x in (A, B, C))
+    lda, ldb, ldc = A.shape[1], B.shape[1], w.N
+    if entry == "config":
+        b.sgemm_run_config(None, cfg, w.M, w.N, w.K, w.alpha, dA, lda, dB, ldb, w.beta, dC, ldc, w.layout)
+    else:
+        b.sgemm_tuned_on(None, w.M, w.N, w.K, w.alpha, dA, lda, dB, ldb, w.beta, dC, ldc, w.layout)
+    torch.cuda.synchronize()
+    got = dC.cpu().numpy()
+    r, c = synth.sample_positions(w.M, w.N, w.seed, rows=rows, cols=cols, scattered=scattered)
+    ref = orc.sgemm_sample(w.alpha, A, B, w.beta, C, r, c, w.layout)
+    tol = orc.tolerance(w.K, np.max(np.abs(A)), np.max(np.abs(B)), ref)
+    err = np.abs(got[r, c].astype(np.float64) - ref)
+    assert np.all(err <= tol), (workload, cfg, float(np.max(err / tol)))
+    # property that holds at any size: nothing non-finite, nothing left unwritten
+    assert np.all(np.isfinite(got))
+    return float(np.max(err / tol))
+
+
+BENCH_CONFIGS = [
+    b.make_config(256, 256, 32, 32, 16, 4, 4, 1, 1, 1, 8, 1, 1),
+    b.make_config(128, 128, 16, 16, 16, 4, 4, 1, 1, 1, 8, 1, 1),
+    b.make_config(64, 64, 16, 8, 8, 4, 4, 1, 1, 1, 8, 0, 1),
+]
+
+
+@pytest.mark.parametrize("which", range(len(BENCH_CONFIGS)))
+def test_headline_size_4096_sampled(which):
+    _sampled_check("cfg4_4096", BENCH_CONFIGS[which])
+
+
+def test_dispatch_entry_point_at_headline_size():
+    _sampled_check("cfg4_4096", None, entry="tuned")
+
+
+@pytest.mark.parametrize("workload", ["cfg5_128x4096x4096", "cfg5_4096x64x9216"])
+def test_deep_learning_shapes_a_transposed(workload):
+    _sampled_check(workload, b.make_config(64, 64, 16, 16, 16, 4, 4, 1, 1, 1, 8, 1, 0), rows=16, cols=16)
+    _sampled_check(workload, None, entry="tuned", rows=16, cols=16)
+
+
+@pytest.mark.parametrize("workload", ["cfg3_1000", "cfg3_1536"])
+def test_non_tile_multiple_sizes_full_compare(workload):
+    w = synth.WORKLOADS[workload]
+    A, B, C = synth.make_workload(w)
+    ref = orc.sgemm(w.alpha, A, B, w.beta, C, w.layout)
+    for cfg in BENCH_CONFIGS:
+        got = gu.run_gpu(cfg, A, B, C, w.alpha, w.beta, w.layout)
+        gu.check_against_oracle(got, A, B, C, w.alpha, w.beta, w.layout, ref, what=f"{workload} {cfg}")
+    got = gu.run_gpu(None, A, B, C, w.alpha, w.beta, w.layout, entry="tuned")
+    gu.check_against_oracle(got, A, B, C, w.alpha, w.beta, w.layout, ref, what=f"{workload} tuned")
