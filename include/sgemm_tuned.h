@@ -97,12 +97,15 @@ typedef struct sgemm_kernel_info {
 /* Options of tune_ex(); zero-initialise and set what you need (0 = default). */
 typedef struct tune_opts {
     int space;          /* SGEMM_SPACE_*; 0 = SGEMM_SPACE_FULL                            */
-    int warmup;         /* untimed launches per configuration; default 2                  */
+    int warmup;         /* minimum untimed launches per configuration; default 2          */
     int reps;           /* timed samples per configuration (median is kept); default 7    */
     int verify_off;     /* 1 = skip the comparison against the reference kernel           */
     float cut_factor;   /* stop timing a configuration whose first sample is slower than
                            cut_factor x the best so far and keep that sample as its time;
                            default 3, negative = never cut                                 */
+    float warmup_ms;    /* keep launching untimed until about this much GPU time has passed
+                           (the clock needs ~20 ms of load to settle); default 25,
+                           negative = none beyond `warmup`                                 */
     float sa_T;         /* annealing temperature (paper: 2, 4, 6); default 4              */
     int sa_raw_ms;      /* 1 = t, t' in raw milliseconds; 0 = percent of best-so-far      */
     int pso_S;          /* swarm size (paper: 3, 6); default 3                            */

@@ -58,6 +58,7 @@ class sgemm_kernel_info(ctypes.Structure):
 class tune_opts(ctypes.Structure):
     _fields_ = [("space", ctypes.c_int), ("warmup", ctypes.c_int), ("reps", ctypes.c_int),
                 ("verify_off", ctypes.c_int), ("cut_factor", ctypes.c_float),
+                ("warmup_ms", ctypes.c_float),
                 ("sa_T", ctypes.c_float), ("sa_raw_ms", ctypes.c_int), ("pso_S", ctypes.c_int),
                 ("pso_alpha", ctypes.c_float), ("pso_beta", ctypes.c_float),
                 ("pso_gamma", ctypes.c_float), ("random_fraction", ctypes.c_float),

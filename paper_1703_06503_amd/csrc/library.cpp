@@ -520,6 +520,7 @@ int tune_ex(int M, int N, int K, int layout, float alpha, float beta, int strate
     const int reps = (opts && opts->reps > 0) ? opts->reps : 7;
     const bool verify = !(opts && opts->verify_off);
     const double cut = (opts && opts->cut_factor != 0.0f) ? opts->cut_factor : 3.0;
+    const double warmup_ms = (opts && opts->warmup_ms != 0.0f) ? opts->warmup_ms : 25.0;
 
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) return SGEMM_E_NODEVICE;
@@ -617,9 +618,18 @@ int tune_ex(int M, int N, int K, int layout, float alpha, float beta, int strate
             if (verify) (void)hipMemcpyAsync(bits, dwords, 8, hipMemcpyDeviceToHost, s);
             if (hipStreamSynchronize(s) != hipSuccess) { status = "fault"; hip_failure = 1; break; }
             if (verify && bits[0] != 0) { status = "verify"; break; }
-            float first = 0.0f;
+            float first = 0.0f; // duration of the verified launch: cold clocks, up to ~1.25x slow
             (void)hipEventElapsedTime(&first, ev0.e, ev1.e);
-            for (int w = 1; w < warmup; ++w) launch();
+            if (cut > 0.0 && best_ms > 0.0 && first > 1.3 * cut * best_ms) {
+                ms = first; // hopeless even allowing for the cold start: not worth warming up
+                samples = 1;
+                status = "ok-cut";
+                break;
+            }
+            int warm = warmup - 1;
+            if (warmup_ms > 0.0 && first > 0.0f)
+                warm = std::max(warm, std::min(4096, (int)std::ceil(warmup_ms / first)));
+            for (int w = 0; w < warm; ++w) launch();
             // short kernels: several launches per sample so that a sample lasts >= 0.2 ms
             int batch = 1;
             if (first > 0.0f && first < 0.2f) batch = std::min(64, (int)std::ceil(0.2f / first));
@@ -633,7 +643,7 @@ int tune_ex(int M, int N, int K, int layout, float alpha, float beta, int strate
                 float e = 0.0f;
                 (void)hipEventElapsedTime(&e, ev0.e, ev1.e);
                 t.push_back((double)e / batch);
-                if (r == 0 && cut > 0.0 && best_ms > 0.0 && t[0] > cut * best_ms) break;
+                if (r == 0 && cut > 0.0 && best_ms > 0.0 && t[0] > cut * best_ms) { status = "ok-cut"; break; }
             }
             if (failed || t.empty()) { status = "fault"; hip_failure = 1; break; }
             samples = (int)t.size();

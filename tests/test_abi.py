@@ -1,0 +1,113 @@
+"""The C-ABI library loads without a GPU and exports every symbol include/sgemm_tuned.h
+declares; host-only entry points answer; argument checks reject bad input before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_1703_06503_amd import binding as b
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "sgemm_tuned.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b([a-z_0-9]+)\s*\(", text)) - {"defined"})
+
+
+def test_every_declared_symbol_is_exported_and_bound():
+    lib = ctypes.CDLL(b.LIB_PATH) if False else b.lib()
+    names = declared_symbols()
+    assert "sgemm_tuned" in names and "tune" in names and len(names) >= 25
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in the header but not exported"
+        assert n in b.EXPORTS, f"{n} has no Python binding"
+        assert callable(getattr(b, n)), n
+    assert sorted(b.EXPORTS) == names
+
+
+def test_status_strings():
+    assert b.sgemm_status_string(0) == "ok"
+    for code in range(-9, 0):
+        assert b.sgemm_status_string(code) not in ("ok", "unknown status")
+    assert b.sgemm_status_string(-99) == "unknown status"
+
+
+def test_struct_sizes_match_the_header():
+    assert ctypes.sizeof(b.sgemm_config) == 16 * 4
+    assert ctypes.sizeof(b.sgemm_kernel_info) == 8 * 4
+    assert ctypes.sizeof(b.tune_result) == 16 * 4 + 9 * 4 + 6 * 4
+
+
+def test_bad_arguments_are_rejected_without_a_gpu():
+    cfg = b.sgemm_config_default(256, 256, 256)
+    with pytest.raises(b.SgemmError) as e:
+        b.sgemm_run_config(0, cfg, -1, 4, 4, 1.0, 0, 4, 0, 4, 0.0, 0, 4, 0)
+    assert e.value.status == b.E_BADARG
+    with pytest.raises(b.SgemmError) as e:      # null C for a non-empty problem
+        b.sgemm_tuned_on(0, 4, 4, 4, 1.0, 1, 4, 1, 4, 0.0, None, 4, 0)
+    assert e.value.status == b.E_BADARG
+    with pytest.raises(b.SgemmError) as e:      # unknown layout
+        b.sgemm_reference(0, 4, 4, 4, 1.0, 1, 4, 1, 4, 0.0, 1, 4, 4)
+    assert e.value.status == b.E_BADARG
+    with pytest.raises(b.SgemmError) as e:
+        b.tune_ex(0, 4, 4, 0, 1.0, 0.0, b.STRATEGY_FULL, 0)
+    assert e.value.status == b.E_BADARG
+    with pytest.raises(b.SgemmError) as e:
+        b.tune_ex(4, 4, 4, 0, 1.0, 0.0, 17, 0)
+    assert e.value.status == b.E_BADARG
+    # empty problems are fine and launch nothing
+    assert b.sgemm_run_config(0, cfg, 0, 4, 4, 1.0, 0, 4, 0, 4, 0.0, 0, 4, 0) == 0
+
+
+def test_kernel_generator_compiles_without_a_gpu(tmp_path):
+    b.sgemm_kernel_cache_dir(str(tmp_path))
+    try:
+        cfg = b.make_config(64, 64, 16, 8, 8, 4, 4, 1, 1, 1, 8, 1, 0)
+        info = b.sgemm_kernel_compile(cfg, 0, 1)
+        assert info.from_cache == 0 and info.code_bytes > 1000 and info.scratch_bytes == 0
+        assert info.lds_bytes == 2 * 4 * (64 * 20 + 16 * 68)        # row-major A and B
+        assert b.sgemm_config_lds_bytes(cfg) == 2 * 4 * (64 * 20 + 64 * 20)   # worst layout
+        assert b.sgemm_kernel_compile(cfg, 2, 0).lds_bytes == 2 * 4 * (64 * 20 + 64 * 20)
+        assert info.agprs + info.vgprs >= 64            # 8 x 8 accumulators per lane
+        again = b.sgemm_kernel_compile(cfg, 0, 1)
+        assert again.from_cache == 1 and again.code_bytes == info.code_bytes
+        macros = b.sgemm_kernel_macros(cfg, 3, 1)
+        assert "-DMWG=64" in macros and "-DTRA=1" in macros and "-DTRB=1" in macros and "-DEDGE=1" in macros
+        bad = b.make_config(64, 64, 16, 8, 8, 4, 4, 0, 1, 1, 8, 1, 0)   # VWM without staging A
+        with pytest.raises(b.SgemmError) as e:
+            b.sgemm_kernel_compile(bad, 0, 0)
+        assert e.value.status == b.E_INVALID
+    finally:
+        b.sgemm_kernel_cache_dir(os.path.join(os.path.dirname(b.LIB_PATH), "kcache"))
+
+
+def test_per_shape_cache_roundtrip(tmp_path):
+    b.sgemm_cache_clear()
+    assert b.sgemm_cache_count() == 0 and b.sgemm_config_get(512, 512, 512, 0) is None
+    c1 = b.make_config(64, 64, 16, 8, 8, 4, 4, 1, 1, 1, 8, 1, 0)
+    c2 = b.make_config(128, 128, 16, 16, 16, 4, 4, 1, 1, 1, 8, 1, 1)
+    b.sgemm_config_set(512, 512, 512, 0, c1, 0.01)
+    b.sgemm_config_set(4096, 4096, 4096, 0, c2, 1.0)
+    assert b.sgemm_config_get(512, 512, 512, 0).as_tuple() == c1.as_tuple()
+    # a miss falls back to the nearest tuned shape of the same layout, then to the default
+    assert b.sgemm_config_select(600, 500, 512, 0).as_tuple() == c1.as_tuple()
+    assert b.sgemm_config_select(3000, 3000, 3000, 0).as_tuple() == c2.as_tuple()
+    assert b.sgemm_config_select(512, 512, 512, 1).as_tuple() == b.sgemm_config_default(512, 512, 512, 1).as_tuple()
+    path = str(tmp_path / "cache.txt")
+    b.sgemm_cache_save(path)
+    b.sgemm_cache_clear()
+    assert b.sgemm_cache_count() == 0
+    b.sgemm_cache_load(path)
+    assert b.sgemm_cache_count() == 2
+    assert b.sgemm_config_get(4096, 4096, 4096, 0).as_tuple() == c2.as_tuple()
+    with pytest.raises(b.SgemmError) as e:
+        b.sgemm_cache_load(str(tmp_path / "missing.txt"))
+    assert e.value.status == b.E_IO
+    bad = b.make_config(100, 64, 16, 8, 8, 1, 1, 1, 1, 0, 2, 0, 0)
+    with pytest.raises(b.SgemmError) as e:
+        b.sgemm_config_set(1, 1, 1, 0, bad, 0.0)
+    assert e.value.status == b.E_INVALID
+    b.sgemm_cache_clear()

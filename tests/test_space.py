@@ -1,0 +1,91 @@
+"""The enumerated search space of the library against an independent enumeration
+(oracle/space_oracle.py), plus brute-force checks of the constraints themselves."""
+import numpy as np
+import pytest
+
+from oracle import space_oracle as so
+from paper_1703_06503_amd import binding as b
+
+
+@pytest.mark.parametrize("preset", [b.SPACE_FULL, b.SPACE_SMALL, b.SPACE_MFMA])
+def test_space_equals_oracle_enumeration(preset):
+    want = so.enumerate_space(preset)
+    n = b.sgemm_space_size(preset)
+    assert n == len(want)
+    assert b.sgemm_space_raw_size(preset) == so.raw_size(preset)
+    assert b.sgemm_space_dims(preset) == len(so.NAMES) == 13
+    for d in range(13):
+        assert b.sgemm_space_values(preset, d) == list(so.VALUES[preset][d])
+    step = 1 if n < 2000 else 7
+    for i in list(range(0, n, step)) + [n - 1]:
+        assert b.sgemm_space_get(preset, i).as_tuple() == want[i], i
+    # find() is the inverse of get()
+    for i in np.random.default_rng(0).choice(n, size=min(n, 200), replace=False):
+        assert b.sgemm_space_find(preset, b.make_config(*want[int(i)])) == int(i)
+
+
+def test_sizes():
+    assert b.sgemm_space_size(b.SPACE_SMALL) == 16          # benchmark configuration 1
+    assert 5000 <= b.sgemm_space_size(b.SPACE_FULL) <= 30000  # "about 10^4"
+    assert b.sgemm_space_raw_size(b.SPACE_FULL) == 4 * 4 * 3 * 2 * 2 * 2 * 2 * 2 * 2 * 2 * 2 * 2 * 2
+
+
+def test_config_check_agrees_with_oracle_on_the_raw_product():
+    """Every point of the raw cartesian product of a preset, valid or not."""
+    import itertools
+    for preset in (b.SPACE_SMALL, b.SPACE_MFMA):
+        pts = list(itertools.product(*so.VALUES[preset]))
+        rng = np.random.default_rng(preset)
+        for k in rng.choice(len(pts), size=min(len(pts), 1500), replace=False):
+            cfg = pts[int(k)]
+            assert (b.sgemm_config_check(b.make_config(*cfg)) == 0) == so.valid(cfg), cfg
+
+
+def test_every_emitted_config_meets_the_device_limits():
+    for preset in (b.SPACE_FULL, b.SPACE_MFMA):
+        n = b.sgemm_space_size(preset)
+        for i in range(0, n, 11):
+            c = b.sgemm_space_get(preset, i)
+            t = c.as_tuple()
+            threads = c.mdimc * c.ndimc
+            assert threads % 64 == 0 and threads <= 1024
+            assert c.mwg % c.mdimc == 0 and c.nwg % c.ndimc == 0 and c.kwg % c.kwi == 0
+            lds = b.sgemm_config_lds_bytes(c)
+            assert lds == so.worst_lds_bytes(t) <= 160 * 1024
+            if c.sa:
+                assert (c.mwg * c.kwg) % (threads * c.vwm) == 0
+            if c.sb:
+                assert (c.nwg * c.kwg) % (threads * c.vwn) == 0
+            if c.mfma:
+                tile = 32 if c.mfma == 1 else 16
+                assert (8 * c.mwg // c.mdimc) % tile == 0 and (8 * c.nwg // c.ndimc) % tile == 0
+
+
+def test_paper_style_best_configs_are_not_rejected_by_divisibility():
+    """The paper's Table IV winners, mapped onto this parameterisation (tile, workgroup shape,
+    vector widths, KWI; both operands staged), satisfy the divisibility constraints; whatever
+    is rejected is rejected for a gfx950 reason (workgroup not a multiple of 64 lanes)."""
+    table4 = {
+        "K40m": (128, 128, 16, 16, 16, 2, 1, 8),
+        "GTX480": (64, 64, 32, 8, 16, 2, 2, 8),
+        "HD7970": (128, 128, 32, 16, 16, 4, 4, 2),
+        "Iris": (64, 64, 16, 8, 8, 4, 4, 8),
+    }
+    for dev, (mwg, nwg, kwg, mdimc, ndimc, vwm, vwn, kwi) in table4.items():
+        cfg = b.make_config(mwg, nwg, kwg, mdimc, ndimc, vwm, vwn, 1, 1, 1, kwi, 0, 0)
+        assert b.sgemm_config_check(cfg) == 0, dev
+        assert so.valid(cfg.as_tuple()), dev
+
+
+def test_invalid_examples():
+    ok = (64, 64, 16, 8, 8, 4, 4, 1, 1, 1, 8, 1, 0)
+    assert b.sgemm_config_check(b.make_config(*ok)) == 0
+    for field, value in [("mwg", 48), ("kwg", 12), ("mdimc", 4), ("vwm", 3), ("kwi", 32),
+                         ("mfma", 3), ("sa", 2), ("mwg", 1024)]:
+        c = b.make_config(*ok)
+        setattr(c, field, value)
+        assert b.sgemm_config_check(c) == b.E_INVALID, (field, value)
+    # LDS capacity: 256 x 256 x 64 tiles double-buffered need 256 KiB
+    big = b.make_config(256, 256, 64, 16, 16, 4, 4, 1, 1, 0, 8, 1, 0)
+    assert b.sgemm_config_lds_bytes(big) == 2 * 4 * (2 * 256 * 64) > 160 * 1024
+    assert b.sgemm_config_check(big) == b.E_INVALID
