@@ -155,6 +155,10 @@ int get_code_object(const VariantKey &key, CodeObject *out, std::string *log) {
     uint64_t h = fnv1a(sgemm_kernel_source_begin, src_len);
     h = fnv1a(macros.data(), macros.size(), h);
     for (const char *f : kCompilerFlags) h = fnv1a(f, std::strlen(f), h);
+    // extra -D options for kernel experiments (space separated); part of the cache key
+    const char *extra_env = std::getenv("SGEMM_TUNED_EXTRA_DEFINES");
+    const std::string extra = extra_env ? extra_env : "";
+    h = fnv1a(extra.data(), extra.size(), h);
     h = compiler_identity(h);
     char name[40];
     std::snprintf(name, sizeof name, "/%016llx.hsaco", (unsigned long long)h);
@@ -178,6 +182,15 @@ int get_code_object(const VariantKey &key, CodeObject *out, std::string *log) {
             size_t sp = macros.find(' ', pos);
             if (sp == std::string::npos) sp = macros.size();
             if (sp > pos) opts.emplace_back(macros.substr(pos, sp - pos));
+            pos = sp + 1;
+        }
+    }
+    {
+        size_t pos = 0;
+        while (pos < extra.size()) {
+            size_t sp = extra.find(' ', pos);
+            if (sp == std::string::npos) sp = extra.size();
+            if (sp > pos) opts.emplace_back(extra.substr(pos, sp - pos));
             pos = sp + 1;
         }
     }
