@@ -23,6 +23,21 @@ if ROOT not in sys.path:
 
 PEAK_FP32_TFLOPS = 157.3   # MI355X published dense FP32 (vector and matrix)
 
+# HBM-side bytes per launch (L2 fetches + writes) from `rocprofv3 --pmc FETCH_SIZE` and
+# `--pmc WRITE_SIZE` runs of this script, each scaled by what the same counter reads for a
+# 64 MiB device-to-device copy (FETCH_SIZE x1.9989, WRITE_SIZE x1.000).  Keyed by workload
+# and by the variant that was timed; the summaries are under profiles/.  A variant that has
+# not been measured reports null.
+MEASURED_TRAFFIC_BYTES = {
+    ("cfg4_4096", (256, 256, 32, 16, 16, 4, 4, 1, 1, 1, 8, 1, 0)): (295454 * 1.9989 + 65536) * 1024,
+}
+
+
+def config_key(cfg):
+    d = cfg.as_dict()
+    return tuple(d[k] for k in ("mwg", "nwg", "kwg", "mdimc", "ndimc", "vwm", "vwn", "sa", "sb",
+                                "pad", "kwi", "mfma", "grp"))
+
 
 def cpu_baseline(w, A, B, C, target_seconds=12.0):
     """The oracle, as it stands, timed on the host cores on a bounded sample of the same
@@ -173,8 +188,11 @@ def main():
         "tuning": tuning,
         "roofline": {"bound": "mfma", "achieved": achieved_tflops, "peak": PEAK_FP32_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved_tflops / PEAK_FP32_TFLOPS,
-                     "traffic": None, "kernel_ms": kernel_ms,
-                     "flops_per_launch": flops},
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((a.workload, config_key(used))),
+                     "traffic_unit": "bytes per launch", "kernel_ms": kernel_ms,
+                     "flops_per_launch": flops,
+                     "algorithmic_bytes": 4.0 * (w.M * w.K + w.K * w.N
+                                                 + w.M * w.N * (2 if w.beta != 0.0 else 1))},
     }
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, A, B, C)
