@@ -59,15 +59,19 @@ extern "C" {
                                LDS staging on/off; everything else fixed */
 #define SGEMM_SPACE_MFMA 2  /* matrix-core variants only, both operands staged, wider value
                                lists (workgroups up to 512 threads, both MFMA shapes) */
+#define SGEMM_SPACE_EXT 3   /* SGEMM_SPACE_MFMA plus tile edges 96 and 192, K slabs of 64 and
+                               split K (sk up to 16): for sizes that powers of two tile badly
+                               and for shapes with few tiles and a long K */
 
 /* One point of the parameter space.  Names follow the paper's GEMM parameters (list in
  * "Tuning parameters" of the matrix-multiplication case study): the workgroup tile
  * Mwg/Nwg/Kwg, the workgroup shape MdimC x NdimC (so each thread owns Mwi = Mwg/MdimC by
  * Nwi = Nwg/NdimC accumulators), the vector widths of the off-chip loads, local-memory
- * staging per operand, and the unroll factor Kwi of the Kwg loop.  `pad`, `mfma` and `grp`
- * are gfx950 additions.  All fields are plain ints so the struct is an int[16]. */
+ * staging per operand, and the unroll factor Kwi of the Kwg loop.  `pad`, `mfma`, `grp` and
+ * `sk` are gfx950 additions.  All fields are plain ints so the struct is an int[16]. */
 typedef struct sgemm_config {
-    int mwg, nwg, kwg; /* workgroup macro-tile of C (mwg x nwg) and K slab per step      */
+    int mwg, nwg, kwg; /* workgroup macro-tile of C (mwg x nwg: each 2^a or 3*2^a) and K slab
+                          per step (power of two)                                          */
     int mdimc, ndimc;  /* threads per workgroup = mdimc * ndimc (multiple of 64)         */
     int vwm;           /* floats per global load of A (1, 2, 4)                          */
     int vwn;           /* floats per global load of B and per store of C (1, 2, 4)       */
@@ -79,7 +83,11 @@ typedef struct sgemm_config {
                           1 = v_mfma_f32_32x32x2_f32 wave tiles,
                           2 = v_mfma_f32_16x16x4_f32 wave tiles                           */
     int grp;           /* 1 = XCD-aware workgroup-to-tile order, 0 = row-major order      */
-    int reserved[3];   /* must be 0                                                        */
+    int sk;            /* split K: sk workgroups per tile of C, each summing a contiguous
+                          1/sk of the K slabs into its own M x N plane of a library-owned
+                          device workspace; a second kernel adds the planes in fixed order
+                          and applies alpha and beta.  0 or 1 = no split.                  */
+    int reserved[2];   /* must be 0                                                        */
 } sgemm_config;
 
 /* What the generator knows about one compiled variant. */

@@ -67,10 +67,11 @@ int load_cache_file_locked(const char *path) {
         int M, N, K, layout;
         float ms;
         Point p;
-        const int got = std::sscanf(line, "%d %d %d %d %f %d %d %d %d %d %d %d %d %d %d %d %d %d", &M,
+        p[13] = 1; // files written before split K existed have no SK column
+        const int got = std::sscanf(line, "%d %d %d %d %f %d %d %d %d %d %d %d %d %d %d %d %d %d %d", &M,
                                     &N, &K, &layout, &ms, &p[0], &p[1], &p[2], &p[3], &p[4], &p[5],
-                                    &p[6], &p[7], &p[8], &p[9], &p[10], &p[11], &p[12]);
-        if (got != 18) continue;
+                                    &p[6], &p[7], &p[8], &p[9], &p[10], &p[11], &p[12], &p[13]);
+        if (got != 18 && got != 19) continue;
         sgemm_config c = from_point(p);
         if (violates(c) || M < 0 || N < 0 || K < 0 || layout < 0 || layout > 3) continue;
         g_tuned[ShapeKey{M, N, K, layout}] = Tuned{c, ms};
@@ -96,6 +97,7 @@ sgemm_config default_config(int M, int N, int K) {
     (void)K;
     sgemm_config c{};
     c.kwg = 16; c.vwm = 4; c.vwn = 4; c.sa = 1; c.sb = 1; c.pad = 1; c.kwi = 8; c.mfma = 1; c.grp = 1;
+    c.sk = 1;
     const long long area = (long long)M * N;
     if (area >= 2048ll * 2048ll) { c.mwg = 128; c.nwg = 128; c.mdimc = 16; c.ndimc = 16; }
     else if (area >= 512ll * 512ll) { c.mwg = 64; c.nwg = 64; c.mdimc = 16; c.ndimc = 16; }
@@ -136,6 +138,10 @@ int check_gemm_args(int M, int N, int K, const float *A, int lda, const float *B
     return SGEMM_OK;
 }
 
+struct SplitPlan;
+SplitPlan plan_split(const sgemm_config &cfg, int K);
+bool splits_k(const sgemm_config &cfg, int K);
+
 bool aligned_for(const void *p, int ld, int vw) {
     return ((uintptr_t)p % (uintptr_t)(4 * vw)) == 0 && (ld % vw) == 0;
 }
@@ -147,12 +153,58 @@ VariantKey resolve_variant(const sgemm_config &cfg, int M, int N, int K, const f
     if (key.cfg.sa && key.cfg.vwm > 1 && !aligned_for(A, lda, key.cfg.vwm)) key.cfg.vwm = 1;
     const bool vwn_loads_b = key.cfg.sb;
     const bool vwn_stores_c = (key.cfg.mfma == 0);
-    if (key.cfg.vwn > 1 && ((vwn_loads_b && !aligned_for(B, ldb, key.cfg.vwn)) ||
-                            (vwn_stores_c && !aligned_for(C, ldc, key.cfg.vwn))))
+    // with split K the variant stores into workspace planes of M x N floats, not into C
+    const bool c_ok = splits_k(cfg, K) ? (N % key.cfg.vwn == 0 && ((long long)M * N) % key.cfg.vwn == 0)
+                                       : aligned_for(C, ldc, key.cfg.vwn);
+    if (key.cfg.vwn > 1 && ((vwn_loads_b && !aligned_for(B, ldb, key.cfg.vwn)) || (vwn_stores_c && !c_ok)))
         key.cfg.vwn = 1;
     key.edge = (M % cfg.mwg || N % cfg.nwg || K % cfg.kwg) ? 1 : 0;
     return key;
 }
+
+// Device workspace for split-K partial planes: one per process, grown on demand and kept.
+// Calls that overlap in time on different streams and both split K would share it, so such
+// calls must be ordered by the caller (the same rule as for any single-workspace library).
+float *g_workspace = nullptr;
+size_t g_workspace_floats = 0;
+
+int workspace_for(size_t floats, float **out) {
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (floats > g_workspace_floats) {
+        // hipFree waits for the device, so no kernel is still using the old buffer
+        if (g_workspace) (void)hipFree(g_workspace);
+        g_workspace = nullptr;
+        g_workspace_floats = 0;
+        void *p = nullptr;
+        const size_t want = std::max(floats, (size_t)(8u << 20)); // at least 32 MiB
+        const hipError_t e = hipMalloc(&p, want * sizeof(float));
+        if (e != hipSuccess) {
+            set_error(std::string("hipMalloc of the split-K workspace: ") + hipGetErrorString(e));
+            return SGEMM_E_LAUNCH;
+        }
+        g_workspace = static_cast<float *>(p);
+        g_workspace_floats = want;
+    }
+    *out = g_workspace;
+    return SGEMM_OK;
+}
+
+// How a configuration's SK is applied to a problem: `parts` workgroups per tile, each summing
+// `k_chunk` consecutive k (a multiple of KWG; the last part takes what is left).
+struct SplitPlan {
+    int parts;
+    int k_chunk;
+};
+
+SplitPlan plan_split(const sgemm_config &cfg, int K) {
+    const int slabs = (K + cfg.kwg - 1) / cfg.kwg;
+    int parts = std::max(1, std::min(cfg.sk, slabs));
+    const int chunk_slabs = (slabs + parts - 1) / parts;
+    parts = (slabs + chunk_slabs - 1) / chunk_slabs; // no empty parts
+    return SplitPlan{parts, parts > 1 ? chunk_slabs * cfg.kwg : K};
+}
+
+bool splits_k(const sgemm_config &cfg, int K) { return plan_split(cfg, K).parts > 1; }
 
 int launch_loaded(hipStream_t s, const LoadedKernel &k, const sgemm_config &cfg, int M, int N, int K,
                   float alpha, const float *A, int lda, const float *B, int ldb, float beta, float *C,
@@ -161,12 +213,36 @@ int launch_loaded(hipStream_t s, const LoadedKernel &k, const sgemm_config &cfg,
     int tiles_n = (N + cfg.nwg - 1) / cfg.nwg;
     const long long wgs = (long long)tiles_m * tiles_n;
     if (wgs > 0x7fffffffll) return SGEMM_E_BADARG;
-    void *args[] = {&M, &N, &K, &alpha, &A, &lda, &B, &ldb, &beta, &C, &ldc, &tiles_m, &tiles_n};
-    const hipError_t e = hipModuleLaunchKernel(k.fn, (unsigned)wgs, 1, 1, (unsigned)k.threads, 1, 1,
-                                               0, s, args, nullptr);
+    const SplitPlan plan = plan_split(cfg, K);
+    int k_chunk = plan.k_chunk;
+    long long split_stride = 0;
+    float *out = C;
+    int ldo = ldc;
+    float a = alpha, b = beta;
+    if (plan.parts > 1) {
+        // every part writes its raw sum into its own plane; the reduction applies alpha, beta
+        const int rc = workspace_for((size_t)plan.parts * (size_t)M * (size_t)N, &out);
+        if (rc != SGEMM_OK) return rc;
+        split_stride = (long long)M * N;
+        ldo = N;
+        a = 1.0f;
+        b = 0.0f;
+    }
+    void *args[] = {&M, &N, &K, &a, &A, &lda, &B, &ldb, &b, &out, &ldo, &tiles_m, &tiles_n,
+                    &k_chunk, &split_stride};
+    const hipError_t e = hipModuleLaunchKernel(k.fn, (unsigned)wgs, (unsigned)plan.parts, 1,
+                                               (unsigned)k.threads, 1, 1, 0, s, args, nullptr);
     if (e != hipSuccess) {
         set_error(std::string("hipModuleLaunchKernel: ") + hipGetErrorString(e));
         return SGEMM_E_LAUNCH;
+    }
+    if (plan.parts > 1) {
+        const hipError_t r = sgemm_util::launch_splitk_reduce(s, M, N, plan.parts, out, (size_t)split_stride,
+                                                              alpha, beta, C, ldc);
+        if (r != hipSuccess) {
+            set_error(std::string("split-K reduction: ") + hipGetErrorString(r));
+            return SGEMM_E_LAUNCH;
+        }
     }
     return SGEMM_OK;
 }
@@ -450,7 +526,7 @@ int sgemm_cache_save(const char *path) {
     autoload_locked();
     FILE *f = std::fopen(path, "w");
     if (!f) return SGEMM_E_IO;
-    std::fprintf(f, "# M N K layout ms MWG NWG KWG MDIMC NDIMC VWM VWN SA SB PAD KWI MFMA GRP\n");
+    std::fprintf(f, "# M N K layout ms MWG NWG KWG MDIMC NDIMC VWM VWN SA SB PAD KWI MFMA GRP SK\n");
     for (auto &kv : g_tuned) {
         const Point p = to_point(kv.second.cfg);
         std::fprintf(f, "%d %d %d %d %.6g", std::get<0>(kv.first), std::get<1>(kv.first),

@@ -5,20 +5,20 @@
 namespace sgemm {
 
 static const char *kNames[kDims] = {"MWG", "NWG", "KWG", "MDIMC", "NDIMC", "VWM", "VWN",
-                                    "SA",  "SB",  "PAD", "KWI",   "MFMA",  "GRP"};
+                                    "SA",  "SB",  "PAD", "KWI",   "MFMA",  "GRP",   "SK"};
 
 const char *dim_name(int d) { return (d >= 0 && d < kDims) ? kNames[d] : "?"; }
 
 Point to_point(const sgemm_config &c) {
     return Point{c.mwg, c.nwg, c.kwg, c.mdimc, c.ndimc, c.vwm, c.vwn,
-                 c.sa,  c.sb,  c.pad, c.kwi,   c.mfma,  c.grp};
+                 c.sa,  c.sb,  c.pad, c.kwi,   c.mfma,  c.grp, c.sk > 0 ? c.sk : 1};
 }
 
 sgemm_config from_point(const Point &p) {
     sgemm_config c{};
     c.mwg = p[0]; c.nwg = p[1]; c.kwg = p[2]; c.mdimc = p[3]; c.ndimc = p[4];
     c.vwm = p[5]; c.vwn = p[6]; c.sa = p[7]; c.sb = p[8]; c.pad = p[9];
-    c.kwi = p[10]; c.mfma = p[11]; c.grp = p[12];
+    c.kwi = p[10]; c.mfma = p[11]; c.grp = p[12]; c.sk = p[13];
     return c;
 }
 
@@ -41,6 +41,14 @@ int lds_bytes(const sgemm_config &c) {
 
 static bool is_pow2_between(int v, int lo, int hi) { return v >= lo && v <= hi && (v & (v - 1)) == 0; }
 
+// Tile edges are 2^a or 3 * 2^a: the second family (96, 192, ...) lets the tile grid fit sizes
+// that powers of two quantise badly (3000 = 15.6 x 192, 1536 = 16 x 96).
+static bool is_tile_edge(int v, int lo, int hi) {
+    if (v < lo || v > hi) return false;
+    if ((v & (v - 1)) == 0) return true;
+    return v % 3 == 0 && ((v / 3) & (v / 3 - 1)) == 0;
+}
+
 // Registers a lane needs at least: accumulators, one KWI block of operand fragments, the
 // global->LDS staging registers, and about 24 for addresses and loop state.
 int estimated_registers(const sgemm_config &c) {
@@ -59,7 +67,7 @@ int estimated_registers(const sgemm_config &c) {
 }
 
 const char *violates(const sgemm_config &c) {
-    if (!is_pow2_between(c.mwg, 8, 512) || !is_pow2_between(c.nwg, 8, 512)) return "tile size";
+    if (!is_tile_edge(c.mwg, 8, 512) || !is_tile_edge(c.nwg, 8, 512)) return "tile size";
     if (!is_pow2_between(c.kwg, 2, 128)) return "KWG";
     if (!is_pow2_between(c.mdimc, 1, 64) || !is_pow2_between(c.ndimc, 1, 64)) return "workgroup shape";
     if (c.vwm != 1 && c.vwm != 2 && c.vwm != 4) return "VWM";
@@ -67,7 +75,8 @@ const char *violates(const sgemm_config &c) {
     if ((c.sa | c.sb | c.pad | c.grp) & ~1) return "flag not 0/1";
     if (c.mfma < 0 || c.mfma > 2) return "MFMA";
     if (!is_pow2_between(c.kwi, 1, 32)) return "KWI";
-    if (c.reserved[0] || c.reserved[1] || c.reserved[2]) return "reserved field set";
+    if (c.sk < 0 || c.sk > kMaxSplitK) return "SK"; // 0 is read as 1
+    if (c.reserved[0] || c.reserved[1]) return "reserved field set";
     const int nt = c.mdimc * c.ndimc;
     // device limit: whole wavefronts, at most 1024 threads
     if (nt % 64 != 0 || nt > kMaxThreads) return "threads per workgroup";
@@ -120,15 +129,21 @@ static Space build(int preset) {
     switch (preset) {
     case SGEMM_SPACE_SMALL:
         // MWG, NWG in {32,64}; KWG in {8,16}; staging on/off for both operands together
-        s.values = {{32, 64}, {32, 64}, {8, 16}, {8}, {8}, {1}, {1}, {0, 1}, {0, 1}, {0}, {2}, {0}, {0}};
+        s.values = {{32, 64}, {32, 64}, {8, 16}, {8}, {8}, {1}, {1}, {0, 1}, {0, 1}, {0}, {2}, {0}, {0}, {1}};
         break;
     case SGEMM_SPACE_FULL:
         s.values = {{32, 64, 128, 256}, {32, 64, 128, 256}, {8, 16, 32}, {8, 16}, {8, 16},
-                    {1, 4}, {1, 4}, {0, 1}, {0, 1}, {0, 1}, {2, 8}, {0, 1}, {0, 1}};
+                    {1, 4}, {1, 4}, {0, 1}, {0, 1}, {0, 1}, {2, 8}, {0, 1}, {0, 1}, {1}};
         break;
     case SGEMM_SPACE_MFMA:
         s.values = {{64, 128, 256}, {64, 128, 256}, {8, 16, 32}, {8, 16, 32}, {8, 16, 32},
-                    {1, 2, 4}, {1, 2, 4}, {1}, {1}, {0, 1}, {2, 8}, {1, 2}, {0, 1}};
+                    {1, 2, 4}, {1, 2, 4}, {1}, {1}, {0, 1}, {2, 8}, {1, 2}, {0, 1}, {1}};
+        break;
+    case SGEMM_SPACE_EXT:
+        // matrix-core variants with tile edges 3 * 2^a as well, deeper K slabs, and split K
+        s.values = {{32, 64, 96, 128, 192, 256}, {32, 64, 96, 128, 192, 256}, {16, 32, 64},
+                    {8, 16, 32}, {8, 16, 32}, {1, 2, 4}, {1, 2, 4}, {1}, {1}, {0, 1}, {2, 8},
+                    {1, 2}, {0, 1}, {1, 2, 3, 4, 6, 8, 12, 16}};
         break;
     default:
         s.preset = -1;

@@ -13,9 +13,10 @@
 
 namespace sgemm {
 
-constexpr int kDims = 13;              // tuned fields of sgemm_config, in field order
+constexpr int kDims = 14;              // tuned fields of sgemm_config, in field order
 constexpr int kLdsLimitBytes = 163840; // LDS per workgroup on gfx950
 constexpr int kMaxThreads = 1024;
+constexpr int kMaxSplitK = 64;         // upper bound of the SK parameter
 
 using Point = std::array<int, kDims>;
 

@@ -2,6 +2,9 @@
 #pragma once
 #include <hip/hip_runtime_api.h>
 
+#include <cstddef>
+#include <cstdint>
+
 namespace sgemm_util {
 
 hipError_t launch_reference(hipStream_t s, int M, int N, int K, float alpha, const float *A,
@@ -17,6 +20,9 @@ hipError_t launch_absmax(hipStream_t s, const float *src, int rows, int cols, in
 // [1] = bit pattern of the largest err / bound.
 hipError_t launch_compare(hipStream_t s, const float *got, int ldg, const float *ref, int ldr,
                           int M, int N, float abs_tol, float rel_tol, unsigned int *two_words);
+// C = alpha * (P[0] + ... + P[planes-1]) + beta * C; P[s] = M x N floats (ld N) at P + s*plane.
+hipError_t launch_splitk_reduce(hipStream_t s, int M, int N, int planes, const float *P,
+                                size_t plane, float alpha, float beta, float *C, int ldc);
 hipError_t launch_copy2d(hipStream_t s, float *dst, int ldd, const float *src, int lds_, int rows,
                          int cols);
 

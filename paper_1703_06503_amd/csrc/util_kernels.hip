@@ -115,6 +115,33 @@ __global__ void copy2d_kernel(float *__restrict__ dst, int ldd, const float *__r
         dst[(e / cols) * ldd + e % cols] = src[(e / cols) * lds_ + e % cols];
 }
 
+// C = alpha * (P[0] + P[1] + ... + P[planes-1]) + beta * C, planes added in index order so the
+// result does not depend on the launch; P[s] is an M x N matrix (leading dimension N) at
+// P + s * plane.  VW floats per thread (4 when N, ldc and both pointers allow 16-byte access).
+template <int VW> struct reduce_vec;
+template <> struct reduce_vec<1> { typedef float type; };
+template <> struct reduce_vec<4> { typedef float type __attribute__((ext_vector_type(4))); };
+
+template <int VW>
+__global__ void splitk_reduce_kernel(int M, int N, int planes, const float *__restrict__ P,
+                                     size_t plane, float alpha, float beta, float *__restrict__ C,
+                                     int ldc) {
+    typedef typename reduce_vec<VW>::type vec;
+    const int nv = N / VW;
+    const size_t n = (size_t)M * nv;
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < n;
+         e += (size_t)gridDim.x * blockDim.x) {
+        const size_t r = e / nv, c = (e % nv) * VW;
+        const float *p = P + r * (size_t)N + c;
+        vec acc = *reinterpret_cast<const vec *>(p);
+        for (int s = 1; s < planes; ++s) acc += *reinterpret_cast<const vec *>(p + (size_t)s * plane);
+        vec *out = reinterpret_cast<vec *>(C + r * (size_t)ldc + c);
+        acc = alpha * acc;
+        if (beta != 0.0f) acc += beta * *out; // C is read only when beta != 0
+        *out = acc;
+    }
+}
+
 __global__ void zero_u32_kernel(unsigned int *p, int n) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = 0u;
@@ -174,6 +201,24 @@ hipError_t launch_compare(hipStream_t s, const float *got, int ldg, const float 
     if (n == 0) return hipGetLastError();
     hipLaunchKernelGGL(compare_kernel, dim3(grid_for(n, 256)), dim3(256), 0, s, got, ldg, ref, ldr,
                        M, N, abs_tol, rel_tol, two_words, two_words + 1);
+    return hipGetLastError();
+}
+
+hipError_t launch_splitk_reduce(hipStream_t s, int M, int N, int planes, const float *P,
+                                size_t plane, float alpha, float beta, float *C, int ldc) {
+    if (M == 0 || N == 0 || planes <= 0) return hipSuccess;
+    const bool wide = N % 4 == 0 && ldc % 4 == 0 && plane % 4 == 0 &&
+                      (reinterpret_cast<uintptr_t>(P) % 16) == 0 &&
+                      (reinterpret_cast<uintptr_t>(C) % 16) == 0;
+    if (wide) {
+        const size_t n = (size_t)M * (N / 4);
+        hipLaunchKernelGGL(splitk_reduce_kernel<4>, dim3(grid_for(n, 256)), dim3(256), 0, s, M, N,
+                           planes, P, plane, alpha, beta, C, ldc);
+    } else {
+        const size_t n = (size_t)M * N;
+        hipLaunchKernelGGL(splitk_reduce_kernel<1>, dim3(grid_for(n, 256)), dim3(256), 0, s, M, N,
+                           planes, P, plane, alpha, beta, C, ldc);
+    }
     return hipGetLastError();
 }
 

@@ -22,9 +22,12 @@ def main():
     precompile(b.SPACE_FULL, (0,), (0, 1), jobs, indices=full)
     mfma = gu.sample_configs(**t.MFMA_SAMPLE)
     precompile(b.SPACE_MFMA, (0,), (0, 1), jobs, indices=mfma)
+    precompile(b.SPACE_EXT, (0,), (0, 1), jobs, indices=gu.sample_configs(**t.EXT_SAMPLE))
     for layout in (1, 2, 3):
         precompile(b.SPACE_FULL, (layout,), (0, 1), jobs,
                    indices=gu.sample_configs(b.SPACE_FULL, 40, seed=100 + layout))
+        precompile(b.SPACE_EXT, (layout,), (1,), jobs,
+                   indices=gu.sample_configs(b.SPACE_EXT, 24, seed=200 + layout))
 
 
 if __name__ == "__main__":

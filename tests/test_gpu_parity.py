@@ -14,6 +14,9 @@ pytestmark = pytest.mark.gpu
 # `tests/precompile_test_variants.py` puts into the kernel cache ahead of time).
 FULL_SAMPLE = dict(space=b.SPACE_FULL, count=160, seed=1234)
 MFMA_SAMPLE = dict(space=b.SPACE_MFMA, count=80, seed=4321)
+EXT_SAMPLE = dict(space=b.SPACE_EXT, count=80, seed=777)   # tile edges 96/192, split K
+EXACT_EXT = (768, 768, 1024)      # multiples of 96, 192 and 256; 16..64 slabs to split
+RAGGED_EXT = (300, 520, 1000)
 EXACT_SHAPE = (256, 512, 96)      # multiples of every tile size: unguarded variants
 RAGGED_SHAPE = (200, 136, 68)     # guarded variants, several tiles for small configs
 RAGGED_BIG = (300, 520, 44)       # more than one tile even at 256 x 256
@@ -58,6 +61,21 @@ def test_mfma_space_sample_ragged():
     _sweep(b.SPACE_MFMA, gu.sample_configs(**MFMA_SAMPLE), RAGGED_BIG, -1.5, 0.25, 0, seed=24)
 
 
+def test_ext_space_sample_exact_tiles():
+    _sweep(b.SPACE_EXT, gu.sample_configs(**EXT_SAMPLE), EXACT_EXT, 1.5, -0.5, 0, seed=25)
+
+
+def test_ext_space_sample_ragged():
+    _sweep(b.SPACE_EXT, gu.sample_configs(**EXT_SAMPLE), RAGGED_EXT, 1.0, 1.0, 0, seed=26,
+           dist="normal")
+
+
+@pytest.mark.parametrize("layout", [1, 2, 3])
+def test_ext_space_transposed_storage(layout):
+    idx = gu.sample_configs(b.SPACE_EXT, 24, seed=200 + layout)
+    _sweep(b.SPACE_EXT, idx, RAGGED_EXT, 0.75, 0.0, layout, seed=70 + layout)
+
+
 @pytest.mark.parametrize("layout", [1, 2, 3])
 def test_transposed_storage(layout):
     idx = gu.sample_configs(b.SPACE_FULL, 40, seed=100 + layout)
@@ -66,28 +84,35 @@ def test_transposed_storage(layout):
 
 
 def _some_configs():
-    """A vector-ALU variant, a 32x32x2 MFMA variant and a 16x16x4 MFMA variant."""
+    """A vector-ALU variant, a 32x32x2 MFMA variant, a 16x16x4 MFMA variant, and three
+    split-K variants (vector ALU, MFMA with a 96-wide tile, MFMA split 16 ways)."""
     return [
         b.make_config(64, 64, 16, 8, 8, 4, 4, 1, 1, 1, 8, 0, 0),
         b.make_config(128, 128, 16, 16, 16, 4, 4, 1, 1, 1, 8, 1, 1),
         b.make_config(64, 64, 16, 16, 16, 2, 2, 1, 1, 0, 8, 2, 1),
+        b.make_config(64, 64, 16, 8, 8, 4, 4, 1, 1, 1, 8, 0, 0, 3),
+        b.make_config(96, 64, 16, 8, 16, 4, 4, 1, 1, 1, 8, 1, 1, 4),
+        b.make_config(32, 32, 8, 8, 8, 1, 1, 1, 1, 0, 2, 1, 0, 16),
     ]
 
 
-@pytest.mark.parametrize("which", [0, 1, 2])
+WHICH = list(range(6))
+
+
+@pytest.mark.parametrize("which", WHICH)
 def test_integer_inputs_are_bit_exact(which):
     """Small-integer operands: every summation order gives the same float, so the GPU must
     equal the oracle exactly, whatever the tiling or MFMA blocking."""
     cfg = _some_configs()[which]
     assert b.sgemm_config_check(cfg) == 0
-    for shape in [(256, 256, 64), (130, 70, 33), (1, 1, 1), (5, 300, 2)]:
+    for shape in [(256, 256, 64), (130, 70, 33), (1, 1, 1), (5, 300, 2), (200, 100, 300)]:
         M, N, K = shape
         A, B, C = synth.make_inputs(M, N, K, 0, seed=50, dist="smallint")
         got = gu.run_gpu(cfg, A, B, C, 2.0, -3.0)
         assert np.array_equal(got.astype(np.float64), orc.sgemm(2.0, A, B, -3.0, C)), shape
 
 
-@pytest.mark.parametrize("which", [0, 1, 2])
+@pytest.mark.parametrize("which", WHICH)
 def test_permutation_matrix_is_bit_exact(which):
     cfg = _some_configs()[which]
     rng = np.random.default_rng(51)
@@ -100,7 +125,7 @@ def test_permutation_matrix_is_bit_exact(which):
     assert np.array_equal(got, B[perm])
 
 
-@pytest.mark.parametrize("which", [0, 1, 2])
+@pytest.mark.parametrize("which", WHICH)
 def test_alpha_beta_edge_cases(which):
     cfg = _some_configs()[which]
     A, B, C = synth.make_inputs(150, 140, 60, 0, seed=52)
@@ -130,7 +155,7 @@ def test_alpha_beta_edge_cases(which):
     gu.check_against_oracle(got, A, B, AB, 1.0, -1.0)
 
 
-@pytest.mark.parametrize("which", [0, 1, 2])
+@pytest.mark.parametrize("which", WHICH)
 def test_leading_dimensions_and_untouched_padding(which):
     """ld > row length, unaligned for vector access; elements of C outside M x N stay
     bit-identical, including guard rows after the matrix."""
@@ -186,8 +211,10 @@ def test_reference_kernel_against_oracle():
         assert np.max(np.abs(got - ref)) <= 2.0 ** -23 * np.max(np.abs(ref))
 
 
-def test_run_to_run_determinism():
-    cfg = _some_configs()[1]
+@pytest.mark.parametrize("which", [1, 4, 5])
+def test_run_to_run_determinism(which):
+    """No atomics anywhere: split-K planes are added in index order."""
+    cfg = _some_configs()[which]
     A, B, C = synth.make_inputs(384, 256, 512, 0, seed=61)
     first = gu.run_gpu(cfg, A, B, C, 1.0, 0.0)
     for _ in range(3):
@@ -240,6 +267,7 @@ def test_dispatch_entry_point_at_headline_size():
 @pytest.mark.parametrize("workload", ["cfg5_128x4096x4096", "cfg5_4096x64x9216"])
 def test_deep_learning_shapes_a_transposed(workload):
     _sampled_check(workload, b.make_config(64, 64, 16, 16, 16, 4, 4, 1, 1, 1, 8, 1, 0), rows=16, cols=16)
+    _sampled_check(workload, b.make_config(64, 64, 32, 16, 16, 4, 4, 1, 1, 1, 8, 1, 0, 8), rows=16, cols=16)
     _sampled_check(workload, None, entry="tuned", rows=16, cols=16)
 
 

@@ -7,16 +7,16 @@ from oracle import space_oracle as so
 from paper_1703_06503_amd import binding as b
 
 
-@pytest.mark.parametrize("preset", [b.SPACE_FULL, b.SPACE_SMALL, b.SPACE_MFMA])
+@pytest.mark.parametrize("preset", [b.SPACE_FULL, b.SPACE_SMALL, b.SPACE_MFMA, b.SPACE_EXT])
 def test_space_equals_oracle_enumeration(preset):
     want = so.enumerate_space(preset)
     n = b.sgemm_space_size(preset)
     assert n == len(want)
     assert b.sgemm_space_raw_size(preset) == so.raw_size(preset)
-    assert b.sgemm_space_dims(preset) == len(so.NAMES) == 13
-    for d in range(13):
+    assert b.sgemm_space_dims(preset) == len(so.NAMES) == 14
+    for d in range(14):
         assert b.sgemm_space_values(preset, d) == list(so.VALUES[preset][d])
-    step = 1 if n < 2000 else 7
+    step = 1 if n < 2000 else (7 if n < 50000 else 101)
     for i in list(range(0, n, step)) + [n - 1]:
         assert b.sgemm_space_get(preset, i).as_tuple() == want[i], i
     # find() is the inverse of get()
@@ -33,18 +33,18 @@ def test_sizes():
 def test_config_check_agrees_with_oracle_on_the_raw_product():
     """Every point of the raw cartesian product of a preset, valid or not."""
     import itertools
-    for preset in (b.SPACE_SMALL, b.SPACE_MFMA):
-        pts = list(itertools.product(*so.VALUES[preset]))
+    for preset in (b.SPACE_SMALL, b.SPACE_MFMA, b.SPACE_EXT):
+        lists = so.VALUES[preset]
         rng = np.random.default_rng(preset)
-        for k in rng.choice(len(pts), size=min(len(pts), 1500), replace=False):
-            cfg = pts[int(k)]
+        for _ in range(1500):
+            cfg = tuple(int(v[rng.integers(len(v))]) for v in lists)
             assert (b.sgemm_config_check(b.make_config(*cfg)) == 0) == so.valid(cfg), cfg
 
 
 def test_every_emitted_config_meets_the_device_limits():
-    for preset in (b.SPACE_FULL, b.SPACE_MFMA):
+    for preset in (b.SPACE_FULL, b.SPACE_MFMA, b.SPACE_EXT):
         n = b.sgemm_space_size(preset)
-        for i in range(0, n, 11):
+        for i in range(0, n, 11 if n < 50000 else 173):
             c = b.sgemm_space_get(preset, i)
             t = c.as_tuple()
             threads = c.mdimc * c.ndimc
@@ -80,8 +80,8 @@ def test_paper_style_best_configs_are_not_rejected_by_divisibility():
 def test_invalid_examples():
     ok = (64, 64, 16, 8, 8, 4, 4, 1, 1, 1, 8, 1, 0)
     assert b.sgemm_config_check(b.make_config(*ok)) == 0
-    for field, value in [("mwg", 48), ("kwg", 12), ("mdimc", 4), ("vwm", 3), ("kwi", 32),
-                         ("mfma", 3), ("sa", 2), ("mwg", 1024)]:
+    for field, value in [("mwg", 80), ("mwg", 48), ("kwg", 12), ("mdimc", 4), ("vwm", 3), ("kwi", 32),
+                         ("mfma", 3), ("sa", 2), ("mwg", 1024), ("sk", -1), ("sk", 65)]:
         c = b.make_config(*ok)
         setattr(c, field, value)
         assert b.sgemm_config_check(c) == b.E_INVALID, (field, value)
