@@ -29,14 +29,14 @@ PEAK_FP32_TFLOPS = 157.3   # MI355X published dense FP32 (vector and matrix)
 # and by the variant that was timed; the summaries are under profiles/.  A variant that has
 # not been measured reports null.
 MEASURED_TRAFFIC_BYTES = {
-    ("cfg4_4096", (256, 256, 32, 16, 16, 4, 4, 1, 1, 1, 8, 1, 0)): (295454 * 1.9989 + 65536) * 1024,
+    ("cfg4_4096", (256, 256, 32, 16, 16, 4, 4, 1, 1, 1, 8, 1, 0, 1)): (295454 * 1.9989 + 65536) * 1024,
 }
 
 
 def config_key(cfg):
     d = cfg.as_dict()
     return tuple(d[k] for k in ("mwg", "nwg", "kwg", "mdimc", "ndimc", "vwm", "vwn", "sa", "sb",
-                                "pad", "kwi", "mfma", "grp"))
+                                "pad", "kwi", "mfma", "grp", "sk"))
 
 
 def cpu_baseline(w, A, B, C, target_seconds=12.0):
