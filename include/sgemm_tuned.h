@@ -59,6 +59,9 @@ extern "C" {
                                LDS staging on/off; everything else fixed */
 #define SGEMM_SPACE_MFMA 2  /* matrix-core variants only, both operands staged, wider value
                                lists (workgroups up to 512 threads, both MFMA shapes) */
+#define SGEMM_SPACE_DIRECT 4 /* matrix-core variants whose tiles reach LDS by LDS-direct loads
+                               (sa = sb = 2), with 2 to 4 LDS buffers per tile (ns), the tile
+                               edges and split-K values of SGEMM_SPACE_EXT */
 #define SGEMM_SPACE_EXT 3   /* SGEMM_SPACE_MFMA plus tile edges 96 and 192, K slabs of 64 and
                                split K (sk up to 16): for sizes that powers of two tile badly
                                and for shapes with few tiles and a long K */
@@ -67,17 +70,20 @@ extern "C" {
  * "Tuning parameters" of the matrix-multiplication case study): the workgroup tile
  * Mwg/Nwg/Kwg, the workgroup shape MdimC x NdimC (so each thread owns Mwi = Mwg/MdimC by
  * Nwi = Nwg/NdimC accumulators), the vector widths of the off-chip loads, local-memory
- * staging per operand, and the unroll factor Kwi of the Kwg loop.  `pad`, `mfma`, `grp` and
- * `sk` are gfx950 additions.  All fields are plain ints so the struct is an int[16]. */
+ * staging per operand, and the unroll factor Kwi of the Kwg loop.  `pad`, `mfma`, `grp`,
+ * `sk` and `ns` are gfx950 additions.  All fields are plain ints so the struct is an int[16]. */
 typedef struct sgemm_config {
     int mwg, nwg, kwg; /* workgroup macro-tile of C (mwg x nwg: each 2^a or 3*2^a) and K slab
                           per step (power of two)                                          */
     int mdimc, ndimc;  /* threads per workgroup = mdimc * ndimc (multiple of 64)         */
     int vwm;           /* floats per global load of A (1, 2, 4)                          */
     int vwn;           /* floats per global load of B and per store of C (1, 2, 4)       */
-    int sa, sb;        /* 1 = stage A / B tiles through LDS (double-buffered), 0 = read
-                          operands straight from global memory                            */
-    int pad;           /* 1 = pad LDS rows by 4 floats (bank-conflict-free fragment reads) */
+    int sa, sb;        /* how the A / B tile reaches the arithmetic: 0 = operands read straight
+                          from global memory, 1 = staged in LDS through registers,
+                          2 = staged in LDS by LDS-direct loads (vw 1 or 4 only; k-fastest
+                          tiles are stored XOR-swizzled instead of padded)                 */
+    int pad;           /* 1 = pad the LDS rows of register-staged tiles by 4 floats
+                          (bank-conflict-free fragment reads)                              */
     int kwi;           /* the KWG loop advances kwi at a time, body unrolled (2 or 8)     */
     int mfma;          /* 0 = per-thread register tile on the vector ALU,
                           1 = v_mfma_f32_32x32x2_f32 wave tiles,
@@ -87,7 +93,10 @@ typedef struct sgemm_config {
                           1/sk of the K slabs into its own M x N plane of a library-owned
                           device workspace; a second kernel adds the planes in fixed order
                           and applies alpha and beta.  0 or 1 = no split.                  */
-    int reserved[2];   /* must be 0                                                        */
+    int ns;            /* LDS buffers per staged tile: 2 (also meant by 0), 3 or 4; more than 2
+                          needs every staged operand to use LDS-direct loads, which then
+                          run ns - 1 K slabs ahead of the arithmetic                       */
+    int reserved[1];   /* must be 0                                                        */
 } sgemm_config;
 
 /* What the generator knows about one compiled variant. */

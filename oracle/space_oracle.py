@@ -7,7 +7,7 @@ strategies and search-space properties").  This file writes out, in plain Python
 lists of this build's three presets and every constraint of its GEMM kernel family, and
 enumerates the product in lexicographic order (first parameter slowest).
 
-Parameters, in order: MWG NWG KWG MDIMC NDIMC VWM VWN SA SB PAD KWI MFMA GRP SK.
+Parameters, in order: MWG NWG KWG MDIMC NDIMC VWM VWN SA SB PAD KWI MFMA GRP SK NS.
 
 parity unpinned: the paper's own count of 241 600 valid GEMM configurations cannot be
 reproduced, because its constraint list is not printed; the counts here are pinned only by
@@ -16,25 +16,29 @@ the independent re-derivation below and by brute-force checks in the tests.
 import itertools
 
 NAMES = ("MWG", "NWG", "KWG", "MDIMC", "NDIMC", "VWM", "VWN", "SA", "SB", "PAD", "KWI", "MFMA",
-         "GRP", "SK")
+         "GRP", "SK", "NS")
 
-SPACE_FULL, SPACE_SMALL, SPACE_MFMA, SPACE_EXT = 0, 1, 2, 3
+SPACE_FULL, SPACE_SMALL, SPACE_MFMA, SPACE_EXT, SPACE_DIRECT = 0, 1, 2, 3, 4
 
 VALUES = {
     SPACE_FULL: ([32, 64, 128, 256], [32, 64, 128, 256], [8, 16, 32], [8, 16], [8, 16], [1, 4],
-                 [1, 4], [0, 1], [0, 1], [0, 1], [2, 8], [0, 1], [0, 1], [1]),
+                 [1, 4], [0, 1], [0, 1], [0, 1], [2, 8], [0, 1], [0, 1], [1], [2]),
     SPACE_SMALL: ([32, 64], [32, 64], [8, 16], [8], [8], [1], [1], [0, 1], [0, 1], [0], [2], [0],
-                  [0], [1]),
+                  [0], [1], [2]),
     SPACE_MFMA: ([64, 128, 256], [64, 128, 256], [8, 16, 32], [8, 16, 32], [8, 16, 32],
-                 [1, 2, 4], [1, 2, 4], [1], [1], [0, 1], [2, 8], [1, 2], [0, 1], [1]),
+                 [1, 2, 4], [1, 2, 4], [1], [1], [0, 1], [2, 8], [1, 2], [0, 1], [1], [2]),
     SPACE_EXT: ([32, 64, 96, 128, 192, 256], [32, 64, 96, 128, 192, 256], [16, 32, 64],
                 [8, 16, 32], [8, 16, 32], [1, 2, 4], [1, 2, 4], [1], [1], [0, 1], [2, 8], [1, 2],
-                [0, 1], [1, 2, 3, 4, 6, 8, 12, 16]),
+                [0, 1], [1, 2, 3, 4, 6, 8, 12, 16], [2]),
+    SPACE_DIRECT: ([32, 64, 96, 128, 192, 256], [32, 64, 96, 128, 192, 256], [16, 32, 64],
+                   [8, 16, 32], [8, 16, 32], [1, 4], [1, 4], [2], [2], [0], [2, 8], [1, 2],
+                   [0, 1], [1, 2, 3, 4, 6, 8, 12, 16], [2, 3, 4]),
 }
 
 LDS_LIMIT = 160 * 1024          # bytes per workgroup on gfx950
 MAX_THREADS = 1024
 MAX_SPLIT_K = 64
+MAX_LOADS_IN_FLIGHT = 63        # a wave's counter of outstanding vector-memory loads
 
 
 def _pow2(v):
@@ -47,16 +51,19 @@ def tile_edge_ok(v):
 
 
 def lds_bytes(cfg, layout):
-    """Two buffers of each staged tile; a tile keeps the stored orientation of its matrix, and
-    PAD adds 4 floats to every tile row."""
+    """NS buffers of each staged tile; a tile keeps the stored orientation of its matrix, and
+    PAD adds 4 floats to every row of a register-staged tile (SA/SB = 1; a tile written by
+    LDS-direct loads, SA/SB = 2, cannot be padded)."""
     MWG, NWG, KWG, _, _, _, _, SA, SB, PAD = cfg[:10]
-    pad = 4 if PAD else 0
+    NS = cfg[14] if len(cfg) > 14 else 2
+    pad_a = 4 if PAD and SA == 1 else 0
+    pad_b = 4 if PAD and SB == 1 else 0
     floats = 0
     if SA:
-        floats += KWG * (MWG + pad) if layout & 1 else MWG * (KWG + pad)
+        floats += KWG * (MWG + pad_a) if layout & 1 else MWG * (KWG + pad_a)
     if SB:
-        floats += NWG * (KWG + pad) if layout & 2 else KWG * (NWG + pad)
-    return 2 * 4 * floats
+        floats += NWG * (KWG + pad_b) if layout & 2 else KWG * (NWG + pad_b)
+    return NS * 4 * floats
 
 
 def worst_lds_bytes(cfg):
@@ -73,9 +80,9 @@ def register_estimate(cfg):
         regs += (8 * MWI // tile + 8 * NWI // tile) * (KWI // depth)   # one fragment block
     else:
         regs += MWI + NWI
-    if SA:
+    if SA == 1:
         regs += MWG * KWG // threads            # global -> LDS staging registers
-    if SB:
+    if SB == 1:
         regs += NWG * KWG // threads
     return regs
 
@@ -83,6 +90,7 @@ def register_estimate(cfg):
 def valid(cfg):
     MWG, NWG, KWG, MDIMC, NDIMC, VWM, VWN, SA, SB, PAD, KWI, MFMA, GRP = cfg[:13]
     SK = cfg[13] if len(cfg) > 13 else 1
+    NS = cfg[14] if len(cfg) > 14 else 2
     if not (tile_edge_ok(MWG) and tile_edge_ok(NWG)):
         return False
     if not (_pow2(KWG) and 2 <= KWG <= 128 and _pow2(MDIMC) and _pow2(NDIMC)
@@ -90,7 +98,9 @@ def valid(cfg):
         return False
     if VWM not in (1, 2, 4) or VWN not in (1, 2, 4) or MFMA not in (0, 1, 2):
         return False
-    if any(f not in (0, 1) for f in (SA, SB, PAD, GRP)) or not 1 <= SK <= MAX_SPLIT_K:
+    if any(f not in (0, 1) for f in (PAD, GRP)) or not 1 <= SK <= MAX_SPLIT_K:
+        return False
+    if SA not in (0, 1, 2) or SB not in (0, 1, 2) or NS not in (2, 3, 4):
         return False
     threads = MDIMC * NDIMC
     if threads % 64 or threads > MAX_THREADS:           # whole wavefronts, device limit
@@ -108,8 +118,24 @@ def valid(cfg):
     if SB:
         if NWG % VWN or KWG % VWN or (NWG * KWG) % (threads * VWN):
             return False
-    if PAD and not (SA or SB):
+    if PAD and SA != 1 and SB != 1:                     # only register-staged tiles are padded
         return False
+    if (SA == 2 and VWM == 2) or (SB == 2 and VWN == 2):   # LDS-direct loads: 4 or 16 bytes
+        return False
+    loads = 0                                           # LDS-direct loads per thread and slab
+    if SA == 2:
+        loads += MWG * KWG // (MDIMC * NDIMC * VWM)
+    if SB == 2:
+        loads += NWG * KWG // (MDIMC * NDIMC * VWN)
+    if loads > MAX_LOADS_IN_FLIGHT:                     # one slab's loads must fit the counter
+        return False
+    if NS > 2:
+        # deeper than double buffering: every staged tile must come by LDS-direct loads, and
+        # the loads of the NS - 2 youngest slabs must fit the wave's counter as well
+        if SA == 1 or SB == 1 or (SA != 2 and SB != 2):
+            return False
+        if (NS - 2) * loads > MAX_LOADS_IN_FLIGHT:
+            return False
     if MFMA == 0:
         if NWI % VWN or MWI * NWI > 64:
             return False

@@ -15,14 +15,14 @@ E_BADARG, E_NOCONFIG, E_COMPILE, E_LAUNCH, E_VERIFY = -1, -2, -3, -4, -5
 E_INVALID, E_IO, E_NODEVICE, E_RESOURCE = -6, -7, -8, -9
 LAYOUT_A_TRANSPOSED, LAYOUT_B_TRANSPOSED = 1, 2
 STRATEGY_FULL, STRATEGY_RANDOM, STRATEGY_ANNEALING, STRATEGY_PSO = 0, 1, 2, 3
-SPACE_FULL, SPACE_SMALL, SPACE_MFMA, SPACE_EXT = 0, 1, 2, 3
+SPACE_FULL, SPACE_SMALL, SPACE_MFMA, SPACE_EXT, SPACE_DIRECT = 0, 1, 2, 3, 4
 
 CONFIG_FIELDS = ("mwg", "nwg", "kwg", "mdimc", "ndimc", "vwm", "vwn", "sa", "sb", "pad", "kwi",
-                 "mfma", "grp", "sk")
+                 "mfma", "grp", "sk", "ns")
 
 
 class sgemm_config(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int) for n in CONFIG_FIELDS] + [("reserved", ctypes.c_int * 2)]
+    _fields_ = [(n, ctypes.c_int) for n in CONFIG_FIELDS] + [("reserved", ctypes.c_int * 1)]
 
     def as_tuple(self):
         return tuple(getattr(self, n) for n in CONFIG_FIELDS)
@@ -35,13 +35,15 @@ class sgemm_config(ctypes.Structure):
 
 
 def make_config(*args, **kw):
-    """sgemm_config from positional values in field order (the last one, sk, may be left out
-    and is then 1), or from keywords."""
+    """sgemm_config from positional values in field order (the last two, sk and ns, may be
+    left out and are then 1 and 2), or from keywords."""
     c = sgemm_config()
-    c.sk = 1
+    c.sk, c.ns = 1, 2
     if args:
-        if len(args) == len(CONFIG_FIELDS) - 1:
+        if len(args) == len(CONFIG_FIELDS) - 2:
             args = tuple(args) + (1,)
+        if len(args) == len(CONFIG_FIELDS) - 1:
+            args = tuple(args) + (2,)
         if len(args) != len(CONFIG_FIELDS):
             raise ValueError("expected %d values" % len(CONFIG_FIELDS))
         kw = dict(zip(CONFIG_FIELDS, args))

@@ -67,11 +67,12 @@ int load_cache_file_locked(const char *path) {
         int M, N, K, layout;
         float ms;
         Point p;
-        p[13] = 1; // files written before split K existed have no SK column
-        const int got = std::sscanf(line, "%d %d %d %d %f %d %d %d %d %d %d %d %d %d %d %d %d %d %d", &M,
+        p[13] = 1; // older files have no SK column ...
+        p[14] = 2; // ... and no NS column
+        const int got = std::sscanf(line, "%d %d %d %d %f %d %d %d %d %d %d %d %d %d %d %d %d %d %d %d", &M,
                                     &N, &K, &layout, &ms, &p[0], &p[1], &p[2], &p[3], &p[4], &p[5],
-                                    &p[6], &p[7], &p[8], &p[9], &p[10], &p[11], &p[12], &p[13]);
-        if (got != 18 && got != 19) continue;
+                                    &p[6], &p[7], &p[8], &p[9], &p[10], &p[11], &p[12], &p[13], &p[14]);
+        if (got < 18 || got > 20) continue;
         sgemm_config c = from_point(p);
         if (violates(c) || M < 0 || N < 0 || K < 0 || layout < 0 || layout > 3) continue;
         g_tuned[ShapeKey{M, N, K, layout}] = Tuned{c, ms};
@@ -97,7 +98,7 @@ sgemm_config default_config(int M, int N, int K) {
     (void)K;
     sgemm_config c{};
     c.kwg = 16; c.vwm = 4; c.vwn = 4; c.sa = 1; c.sb = 1; c.pad = 1; c.kwi = 8; c.mfma = 1; c.grp = 1;
-    c.sk = 1;
+    c.sk = 1; c.ns = 2;
     const long long area = (long long)M * N;
     if (area >= 2048ll * 2048ll) { c.mwg = 128; c.nwg = 128; c.mdimc = 16; c.ndimc = 16; }
     else if (area >= 512ll * 512ll) { c.mwg = 64; c.nwg = 64; c.mdimc = 16; c.ndimc = 16; }
@@ -159,6 +160,21 @@ VariantKey resolve_variant(const sgemm_config &cfg, int M, int N, int K, const f
     if (key.cfg.vwn > 1 && ((vwn_loads_b && !aligned_for(B, ldb, key.cfg.vwn)) || (vwn_stores_c && !c_ok)))
         key.cfg.vwn = 1;
     key.edge = (M % cfg.mwg || N % cfg.nwg || K % cfg.kwg) ? 1 : 0;
+    if (key.cfg.ns == 0) key.cfg.ns = 2;
+    // a guarded LDS-direct load replaces whole vectors by zeros, so a stored row must not end
+    // inside one; narrower loads mean more of them, which may not leave room for 3 or 4 buffers
+    if (key.edge) {
+        if (key.cfg.sa == 2 && ((layout & 1) ? M : K) % key.cfg.vwm) key.cfg.vwm = 1;
+        if (key.cfg.sb == 2 && ((layout & 2) ? K : N) % key.cfg.vwn) key.cfg.vwn = 1;
+    }
+    while (key.cfg.ns > 2 && (key.cfg.ns - 2) * direct_loads_per_slab(key.cfg) > kMaxLoadsInFlight)
+        --key.cfg.ns;
+    // narrowed loads that no longer fit the counter at all: stage through registers instead
+    if (direct_loads_per_slab(key.cfg) > kMaxLoadsInFlight) {
+        if (key.cfg.sa == 2) key.cfg.sa = 1;
+        if (key.cfg.sb == 2) key.cfg.sb = 1;
+        key.cfg.ns = 2;
+    }
     return key;
 }
 
@@ -526,7 +542,7 @@ int sgemm_cache_save(const char *path) {
     autoload_locked();
     FILE *f = std::fopen(path, "w");
     if (!f) return SGEMM_E_IO;
-    std::fprintf(f, "# M N K layout ms MWG NWG KWG MDIMC NDIMC VWM VWN SA SB PAD KWI MFMA GRP SK\n");
+    std::fprintf(f, "# M N K layout ms MWG NWG KWG MDIMC NDIMC VWM VWN SA SB PAD KWI MFMA GRP SK NS\n");
     for (auto &kv : g_tuned) {
         const Point p = to_point(kv.second.cfg);
         std::fprintf(f, "%d %d %d %d %.6g", std::get<0>(kv.first), std::get<1>(kv.first),

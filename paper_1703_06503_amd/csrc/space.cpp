@@ -5,29 +5,30 @@
 namespace sgemm {
 
 static const char *kNames[kDims] = {"MWG", "NWG", "KWG", "MDIMC", "NDIMC", "VWM", "VWN",
-                                    "SA",  "SB",  "PAD", "KWI",   "MFMA",  "GRP",   "SK"};
+                                    "SA",  "SB",  "PAD", "KWI",   "MFMA",  "GRP",   "SK",  "NS"};
 
 const char *dim_name(int d) { return (d >= 0 && d < kDims) ? kNames[d] : "?"; }
 
 Point to_point(const sgemm_config &c) {
     return Point{c.mwg, c.nwg, c.kwg, c.mdimc, c.ndimc, c.vwm, c.vwn,
-                 c.sa,  c.sb,  c.pad, c.kwi,   c.mfma,  c.grp, c.sk > 0 ? c.sk : 1};
+                 c.sa,  c.sb,  c.pad, c.kwi,   c.mfma,  c.grp, c.sk > 0 ? c.sk : 1, c.ns > 0 ? c.ns : 2};
 }
 
 sgemm_config from_point(const Point &p) {
     sgemm_config c{};
     c.mwg = p[0]; c.nwg = p[1]; c.kwg = p[2]; c.mdimc = p[3]; c.ndimc = p[4];
     c.vwm = p[5]; c.vwn = p[6]; c.sa = p[7]; c.sb = p[8]; c.pad = p[9];
-    c.kwi = p[10]; c.mfma = p[11]; c.grp = p[12]; c.sk = p[13];
+    c.kwi = p[10]; c.mfma = p[11]; c.grp = p[12]; c.sk = p[13]; c.ns = p[14];
     return c;
 }
 
 int lds_bytes(const sgemm_config &c, int layout) {
-    const int pad = c.pad ? 4 : 0;
+    // only register-staged tiles can be padded; LDS-direct tiles are dense
+    const int pad_a = (c.pad && c.sa == 1) ? 4 : 0, pad_b = (c.pad && c.sb == 1) ? 4 : 0;
     int words = 0;
-    if (c.sa) words += (layout & 1) ? c.kwg * (c.mwg + pad) : c.mwg * (c.kwg + pad);
-    if (c.sb) words += (layout & 2) ? c.nwg * (c.kwg + pad) : c.kwg * (c.nwg + pad);
-    return 2 * 4 * words; // two buffers of floats
+    if (c.sa) words += (layout & 1) ? c.kwg * (c.mwg + pad_a) : c.mwg * (c.kwg + pad_a);
+    if (c.sb) words += (layout & 2) ? c.nwg * (c.kwg + pad_b) : c.kwg * (c.nwg + pad_b);
+    return (c.ns > 0 ? c.ns : 2) * 4 * words; // ns buffers of floats
 }
 
 int lds_bytes(const sgemm_config &c) {
@@ -61,9 +62,17 @@ int estimated_registers(const sgemm_config &c) {
     } else {
         regs += mwi + nwi;
     }
-    if (c.sa) regs += c.mwg * c.kwg / nt;
-    if (c.sb) regs += c.nwg * c.kwg / nt;
+    if (c.sa == 1) regs += c.mwg * c.kwg / nt;
+    if (c.sb == 1) regs += c.nwg * c.kwg / nt;
     return regs;
+}
+
+int direct_loads_per_slab(const sgemm_config &c) {
+    const int nt = c.mdimc * c.ndimc;
+    int ops = 0;
+    if (c.sa == 2) ops += c.mwg * c.kwg / (nt * c.vwm);
+    if (c.sb == 2) ops += c.nwg * c.kwg / (nt * c.vwn);
+    return ops;
 }
 
 const char *violates(const sgemm_config &c) {
@@ -72,11 +81,13 @@ const char *violates(const sgemm_config &c) {
     if (!is_pow2_between(c.mdimc, 1, 64) || !is_pow2_between(c.ndimc, 1, 64)) return "workgroup shape";
     if (c.vwm != 1 && c.vwm != 2 && c.vwm != 4) return "VWM";
     if (c.vwn != 1 && c.vwn != 2 && c.vwn != 4) return "VWN";
-    if ((c.sa | c.sb | c.pad | c.grp) & ~1) return "flag not 0/1";
+    if ((c.pad | c.grp) & ~1) return "flag not 0/1";
+    if (c.sa < 0 || c.sa > 2 || c.sb < 0 || c.sb > 2) return "SA/SB";
+    if (c.ns != 0 && (c.ns < 2 || c.ns > 4)) return "NS"; // 0 is read as 2
     if (c.mfma < 0 || c.mfma > 2) return "MFMA";
     if (!is_pow2_between(c.kwi, 1, 32)) return "KWI";
     if (c.sk < 0 || c.sk > kMaxSplitK) return "SK"; // 0 is read as 1
-    if (c.reserved[0] || c.reserved[1]) return "reserved field set";
+    if (c.reserved[0]) return "reserved field set";
     const int nt = c.mdimc * c.ndimc;
     // device limit: whole wavefronts, at most 1024 threads
     if (nt % 64 != 0 || nt > kMaxThreads) return "threads per workgroup";
@@ -93,7 +104,16 @@ const char *violates(const sgemm_config &c) {
         if (c.nwg % c.vwn || c.kwg % c.vwn) return "B tile row not divisible by VWN";
         if ((c.nwg * c.kwg) % (nt * c.vwn)) return "B tile not divisible among threads";
     }
-    if (!c.sa && !c.sb && c.pad) return "PAD without LDS";
+    if (c.pad && c.sa != 1 && c.sb != 1) return "PAD without a register-staged tile";
+    // LDS-direct loads move 4 or 16 bytes per lane
+    if ((c.sa == 2 && c.vwm == 2) || (c.sb == 2 && c.vwn == 2)) return "LDS-direct load width";
+    // a wave counts at most kMaxLoadsInFlight outstanding loads: one slab's LDS-direct loads,
+    // and with more than two buffers those of the ns - 2 youngest slabs, must fit
+    if (direct_loads_per_slab(c) > kMaxLoadsInFlight) return "loads in flight";
+    if (c.ns > 2) {
+        if (c.sa == 1 || c.sb == 1 || (c.sa != 2 && c.sb != 2)) return "NS > 2 without LDS-direct staging";
+        if ((c.ns - 2) * direct_loads_per_slab(c) > kMaxLoadsInFlight) return "loads in flight";
+    }
     if (c.mfma == 0) {
         if (nwi % c.vwn) return "NWI not divisible by VWN";
         if (mwi * nwi > 64) return "register tile too large";
@@ -129,21 +149,27 @@ static Space build(int preset) {
     switch (preset) {
     case SGEMM_SPACE_SMALL:
         // MWG, NWG in {32,64}; KWG in {8,16}; staging on/off for both operands together
-        s.values = {{32, 64}, {32, 64}, {8, 16}, {8}, {8}, {1}, {1}, {0, 1}, {0, 1}, {0}, {2}, {0}, {0}, {1}};
+        s.values = {{32, 64}, {32, 64}, {8, 16}, {8}, {8}, {1}, {1}, {0, 1}, {0, 1}, {0}, {2}, {0}, {0}, {1}, {2}};
         break;
     case SGEMM_SPACE_FULL:
         s.values = {{32, 64, 128, 256}, {32, 64, 128, 256}, {8, 16, 32}, {8, 16}, {8, 16},
-                    {1, 4}, {1, 4}, {0, 1}, {0, 1}, {0, 1}, {2, 8}, {0, 1}, {0, 1}, {1}};
+                    {1, 4}, {1, 4}, {0, 1}, {0, 1}, {0, 1}, {2, 8}, {0, 1}, {0, 1}, {1}, {2}};
         break;
     case SGEMM_SPACE_MFMA:
         s.values = {{64, 128, 256}, {64, 128, 256}, {8, 16, 32}, {8, 16, 32}, {8, 16, 32},
-                    {1, 2, 4}, {1, 2, 4}, {1}, {1}, {0, 1}, {2, 8}, {1, 2}, {0, 1}, {1}};
+                    {1, 2, 4}, {1, 2, 4}, {1}, {1}, {0, 1}, {2, 8}, {1, 2}, {0, 1}, {1}, {2}};
         break;
     case SGEMM_SPACE_EXT:
         // matrix-core variants with tile edges 3 * 2^a as well, deeper K slabs, and split K
         s.values = {{32, 64, 96, 128, 192, 256}, {32, 64, 96, 128, 192, 256}, {16, 32, 64},
                     {8, 16, 32}, {8, 16, 32}, {1, 2, 4}, {1, 2, 4}, {1}, {1}, {0, 1}, {2, 8},
-                    {1, 2}, {0, 1}, {1, 2, 3, 4, 6, 8, 12, 16}};
+                    {1, 2}, {0, 1}, {1, 2, 3, 4, 6, 8, 12, 16}, {2}};
+        break;
+    case SGEMM_SPACE_DIRECT:
+        // matrix-core variants fed by LDS-direct loads, 2 to 4 LDS buffers per tile
+        s.values = {{32, 64, 96, 128, 192, 256}, {32, 64, 96, 128, 192, 256}, {16, 32, 64},
+                    {8, 16, 32}, {8, 16, 32}, {1, 4}, {1, 4}, {2}, {2}, {0}, {2, 8},
+                    {1, 2}, {0, 1}, {1, 2, 3, 4, 6, 8, 12, 16}, {2, 3, 4}};
         break;
     default:
         s.preset = -1;

@@ -13,10 +13,11 @@
 
 namespace sgemm {
 
-constexpr int kDims = 14;              // tuned fields of sgemm_config, in field order
+constexpr int kDims = 15;              // tuned fields of sgemm_config, in field order
 constexpr int kLdsLimitBytes = 163840; // LDS per workgroup on gfx950
 constexpr int kMaxThreads = 1024;
-constexpr int kMaxSplitK = 64;         // upper bound of the SK parameter
+constexpr int kMaxSplitK = 64;
+constexpr int kMaxLoadsInFlight = 63;  // the vmcnt counter of a wave         // upper bound of the SK parameter
 
 using Point = std::array<int, kDims>;
 
@@ -28,6 +29,7 @@ const char *dim_name(int d);
 int lds_bytes(const sgemm_config &c);       // worst case over the four storage layouts
 int lds_bytes(const sgemm_config &c, int layout);
 int estimated_registers(const sgemm_config &c);
+int direct_loads_per_slab(const sgemm_config &c); // LDS-direct load instructions per thread
 
 // nullptr if c satisfies every constraint, else a short reason.
 const char *violates(const sgemm_config &c);

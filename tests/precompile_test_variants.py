@@ -23,11 +23,14 @@ def main():
     mfma = gu.sample_configs(**t.MFMA_SAMPLE)
     precompile(b.SPACE_MFMA, (0,), (0, 1), jobs, indices=mfma)
     precompile(b.SPACE_EXT, (0,), (0, 1), jobs, indices=gu.sample_configs(**t.EXT_SAMPLE))
+    precompile(b.SPACE_DIRECT, (0,), (0, 1), jobs, indices=gu.sample_configs(**t.DIRECT_SAMPLE))
     for layout in (1, 2, 3):
         precompile(b.SPACE_FULL, (layout,), (0, 1), jobs,
                    indices=gu.sample_configs(b.SPACE_FULL, 40, seed=100 + layout))
         precompile(b.SPACE_EXT, (layout,), (1,), jobs,
                    indices=gu.sample_configs(b.SPACE_EXT, 24, seed=200 + layout))
+        precompile(b.SPACE_DIRECT, (layout,), (0, 1), jobs,
+                   indices=gu.sample_configs(b.SPACE_DIRECT, 24, seed=300 + layout))
 
 
 if __name__ == "__main__":

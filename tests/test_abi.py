@@ -76,6 +76,16 @@ def test_kernel_generator_compiles_without_a_gpu(tmp_path):
         assert again.from_cache == 1 and again.code_bytes == info.code_bytes
         macros = b.sgemm_kernel_macros(cfg, 3, 1)
         assert "-DMWG=64" in macros and "-DTRA=1" in macros and "-DTRB=1" in macros and "-DEDGE=1" in macros
+        # LDS-direct staging with three buffers: dense (unpadded) tiles, NS of them
+        direct = b.make_config(64, 64, 16, 8, 8, 4, 4, 2, 2, 0, 8, 1, 0, 1, 3)
+        dinfo = b.sgemm_kernel_compile(direct, 0, 0)
+        assert dinfo.lds_bytes == 3 * 4 * (64 * 16 + 16 * 64) and dinfo.scratch_bytes == 0
+        assert "-DSA=2" in b.sgemm_kernel_macros(direct, 0, 0)
+        assert "-DNS=3" in b.sgemm_kernel_macros(direct, 0, 0)
+        assert b.sgemm_kernel_compile(direct, 1, 1).scratch_bytes == 0      # guarded form
+        # split K is applied at launch: it is not part of what is compiled
+        split = b.make_config(64, 64, 16, 8, 8, 4, 4, 1, 1, 1, 8, 1, 0, 8)
+        assert b.sgemm_kernel_macros(split, 0, 0) == b.sgemm_kernel_macros(cfg, 0, 0)
         bad = b.make_config(64, 64, 16, 8, 8, 4, 4, 0, 1, 1, 8, 1, 0)   # VWM without staging A
         with pytest.raises(b.SgemmError) as e:
             b.sgemm_kernel_compile(bad, 0, 0)
@@ -88,7 +98,7 @@ def test_per_shape_cache_roundtrip(tmp_path):
     b.sgemm_cache_clear()
     assert b.sgemm_cache_count() == 0 and b.sgemm_config_get(512, 512, 512, 0) is None
     c1 = b.make_config(64, 64, 16, 8, 8, 4, 4, 1, 1, 1, 8, 1, 0)
-    c2 = b.make_config(128, 128, 16, 16, 16, 4, 4, 1, 1, 1, 8, 1, 1)
+    c2 = b.make_config(128, 128, 16, 16, 16, 4, 4, 2, 2, 0, 8, 1, 1, 4, 3)   # split K, 3 buffers
     b.sgemm_config_set(512, 512, 512, 0, c1, 0.01)
     b.sgemm_config_set(4096, 4096, 4096, 0, c2, 1.0)
     assert b.sgemm_config_get(512, 512, 512, 0).as_tuple() == c1.as_tuple()
@@ -103,6 +113,13 @@ def test_per_shape_cache_roundtrip(tmp_path):
     b.sgemm_cache_load(path)
     assert b.sgemm_cache_count() == 2
     assert b.sgemm_config_get(4096, 4096, 4096, 0).as_tuple() == c2.as_tuple()
+    # a table written before the SK and NS columns existed still loads (SK = 1, NS = 2)
+    old = tmp_path / "old.txt"
+    old.write_text("# M N K layout ms MWG NWG KWG MDIMC NDIMC VWM VWN SA SB PAD KWI MFMA GRP\n"
+                   "1024 1024 1024 0 0.05 128 128 16 16 16 4 4 1 1 1 8 1 1\n")
+    b.sgemm_cache_load(str(old))
+    got = b.sgemm_config_get(1024, 1024, 1024, 0)
+    assert got.as_tuple() == (128, 128, 16, 16, 16, 4, 4, 1, 1, 1, 8, 1, 1, 1, 2)
     with pytest.raises(b.SgemmError) as e:
         b.sgemm_cache_load(str(tmp_path / "missing.txt"))
     assert e.value.status == b.E_IO

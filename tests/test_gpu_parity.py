@@ -15,6 +15,7 @@ pytestmark = pytest.mark.gpu
 FULL_SAMPLE = dict(space=b.SPACE_FULL, count=160, seed=1234)
 MFMA_SAMPLE = dict(space=b.SPACE_MFMA, count=80, seed=4321)
 EXT_SAMPLE = dict(space=b.SPACE_EXT, count=80, seed=777)   # tile edges 96/192, split K
+DIRECT_SAMPLE = dict(space=b.SPACE_DIRECT, count=80, seed=555)   # LDS-direct staging, 2-4 buffers
 EXACT_EXT = (768, 768, 1024)      # multiples of 96, 192 and 256; 16..64 slabs to split
 RAGGED_EXT = (300, 520, 1000)
 EXACT_SHAPE = (256, 512, 96)      # multiples of every tile size: unguarded variants
@@ -70,6 +71,25 @@ def test_ext_space_sample_ragged():
            dist="normal")
 
 
+def test_direct_space_sample_exact_tiles():
+    _sweep(b.SPACE_DIRECT, gu.sample_configs(**DIRECT_SAMPLE), EXACT_EXT, 1.0, 0.0, 0, seed=27,
+           dist="normal")
+
+
+def test_direct_space_sample_ragged():
+    idx = gu.sample_configs(**DIRECT_SAMPLE)
+    _sweep(b.SPACE_DIRECT, idx, RAGGED_EXT, 2.0, 0.5, 0, seed=28)
+    # odd sizes: the stored rows end inside a 16-byte vector, so the loads are narrowed
+    _sweep(b.SPACE_DIRECT, idx[::4], (203, 137, 67), 1.0, 1.0, 0, seed=29)
+
+
+@pytest.mark.parametrize("layout", [1, 2, 3])
+def test_direct_space_transposed_storage(layout):
+    idx = gu.sample_configs(b.SPACE_DIRECT, 24, seed=300 + layout)
+    _sweep(b.SPACE_DIRECT, idx, EXACT_EXT, 1.0, 0.0, layout, seed=80 + layout)
+    _sweep(b.SPACE_DIRECT, idx, RAGGED_EXT, -1.0, 0.5, layout, seed=90 + layout)
+
+
 @pytest.mark.parametrize("layout", [1, 2, 3])
 def test_ext_space_transposed_storage(layout):
     idx = gu.sample_configs(b.SPACE_EXT, 24, seed=200 + layout)
@@ -85,7 +105,9 @@ def test_transposed_storage(layout):
 
 def _some_configs():
     """A vector-ALU variant, a 32x32x2 MFMA variant, a 16x16x4 MFMA variant, and three
-    split-K variants (vector ALU, MFMA with a 96-wide tile, MFMA split 16 ways)."""
+    split-K variants (vector ALU, MFMA with a 96-wide tile, MFMA split 16 ways), and three
+    variants fed by LDS-direct loads (three LDS buffers; four buffers with split K; vector ALU
+    with A direct and B through registers)."""
     return [
         b.make_config(64, 64, 16, 8, 8, 4, 4, 1, 1, 1, 8, 0, 0),
         b.make_config(128, 128, 16, 16, 16, 4, 4, 1, 1, 1, 8, 1, 1),
@@ -93,10 +115,13 @@ def _some_configs():
         b.make_config(64, 64, 16, 8, 8, 4, 4, 1, 1, 1, 8, 0, 0, 3),
         b.make_config(96, 64, 16, 8, 16, 4, 4, 1, 1, 1, 8, 1, 1, 4),
         b.make_config(32, 32, 8, 8, 8, 1, 1, 1, 1, 0, 2, 1, 0, 16),
+        b.make_config(128, 128, 16, 16, 16, 4, 4, 2, 2, 0, 8, 1, 1, 1, 3),
+        b.make_config(64, 64, 32, 8, 8, 4, 4, 2, 2, 0, 8, 2, 0, 2, 4),
+        b.make_config(64, 64, 16, 8, 8, 4, 4, 2, 1, 1, 8, 0, 0, 1, 2),
     ]
 
 
-WHICH = list(range(6))
+WHICH = list(range(9))
 
 
 @pytest.mark.parametrize("which", WHICH)
@@ -161,7 +186,13 @@ def test_leading_dimensions_and_untouched_padding(which):
     bit-identical, including guard rows after the matrix."""
     import torch
     cfg = _some_configs()[which]
-    M, N, K, lda, ldb, ldc = 97, 83, 45, 51, 90, 89
+    _check_leading_dimensions(cfg, 97, 83, 45, 51, 90, 89)
+    # aligned leading dimensions, but rows that end inside a 16-byte vector
+    _check_leading_dimensions(cfg, 97, 83, 45, 48, 84, 84)
+
+
+def _check_leading_dimensions(cfg, M, N, K, lda, ldb, ldc):
+    import torch
     rng = np.random.default_rng(53)
     Abuf = rng.uniform(-1, 1, (M, lda)).astype(np.float32)
     Bbuf = rng.uniform(-1, 1, (K, ldb)).astype(np.float32)
@@ -211,7 +242,7 @@ def test_reference_kernel_against_oracle():
         assert np.max(np.abs(got - ref)) <= 2.0 ** -23 * np.max(np.abs(ref))
 
 
-@pytest.mark.parametrize("which", [1, 4, 5])
+@pytest.mark.parametrize("which", [1, 4, 5, 7])
 def test_run_to_run_determinism(which):
     """No atomics anywhere: split-K planes are added in index order."""
     cfg = _some_configs()[which]
@@ -250,6 +281,7 @@ def _sampled_check(workload, cfg, entry="config", rows=64, cols=64, scattered=40
 
 BENCH_CONFIGS = [
     b.make_config(256, 256, 32, 32, 16, 4, 4, 1, 1, 1, 8, 1, 1),
+    b.make_config(256, 256, 32, 16, 16, 4, 4, 2, 2, 0, 8, 1, 1, 1, 2),
     b.make_config(128, 128, 16, 16, 16, 4, 4, 1, 1, 1, 8, 1, 1),
     b.make_config(64, 64, 16, 8, 8, 4, 4, 1, 1, 1, 8, 0, 1),
 ]

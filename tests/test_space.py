@@ -7,14 +7,15 @@ from oracle import space_oracle as so
 from paper_1703_06503_amd import binding as b
 
 
-@pytest.mark.parametrize("preset", [b.SPACE_FULL, b.SPACE_SMALL, b.SPACE_MFMA, b.SPACE_EXT])
+@pytest.mark.parametrize("preset", [b.SPACE_FULL, b.SPACE_SMALL, b.SPACE_MFMA, b.SPACE_EXT,
+                                    b.SPACE_DIRECT])
 def test_space_equals_oracle_enumeration(preset):
     want = so.enumerate_space(preset)
     n = b.sgemm_space_size(preset)
     assert n == len(want)
     assert b.sgemm_space_raw_size(preset) == so.raw_size(preset)
-    assert b.sgemm_space_dims(preset) == len(so.NAMES) == 14
-    for d in range(14):
+    assert b.sgemm_space_dims(preset) == len(so.NAMES) == 15
+    for d in range(15):
         assert b.sgemm_space_values(preset, d) == list(so.VALUES[preset][d])
     step = 1 if n < 2000 else (7 if n < 50000 else 101)
     for i in list(range(0, n, step)) + [n - 1]:
@@ -33,7 +34,7 @@ def test_sizes():
 def test_config_check_agrees_with_oracle_on_the_raw_product():
     """Every point of the raw cartesian product of a preset, valid or not."""
     import itertools
-    for preset in (b.SPACE_SMALL, b.SPACE_MFMA, b.SPACE_EXT):
+    for preset in (b.SPACE_SMALL, b.SPACE_MFMA, b.SPACE_EXT, b.SPACE_DIRECT):
         lists = so.VALUES[preset]
         rng = np.random.default_rng(preset)
         for _ in range(1500):
@@ -42,7 +43,7 @@ def test_config_check_agrees_with_oracle_on_the_raw_product():
 
 
 def test_every_emitted_config_meets_the_device_limits():
-    for preset in (b.SPACE_FULL, b.SPACE_MFMA, b.SPACE_EXT):
+    for preset in (b.SPACE_FULL, b.SPACE_MFMA, b.SPACE_EXT, b.SPACE_DIRECT):
         n = b.sgemm_space_size(preset)
         for i in range(0, n, 11 if n < 50000 else 173):
             c = b.sgemm_space_get(preset, i)
@@ -81,7 +82,8 @@ def test_invalid_examples():
     ok = (64, 64, 16, 8, 8, 4, 4, 1, 1, 1, 8, 1, 0)
     assert b.sgemm_config_check(b.make_config(*ok)) == 0
     for field, value in [("mwg", 80), ("mwg", 48), ("kwg", 12), ("mdimc", 4), ("vwm", 3), ("kwi", 32),
-                         ("mfma", 3), ("sa", 2), ("mwg", 1024), ("sk", -1), ("sk", 65)]:
+                         ("mfma", 3), ("sa", 3), ("mwg", 1024), ("sk", -1), ("sk", 65), ("ns", 1), ("ns", 5),
+                         ("ns", 3)]:      # three buffers need LDS-direct staging
         c = b.make_config(*ok)
         setattr(c, field, value)
         assert b.sgemm_config_check(c) == b.E_INVALID, (field, value)
