@@ -214,13 +214,21 @@ int sgemm_space_values(int space, int dim, int *values, int cap);
 int sgemm_config_check(const sgemm_config *cfg);
 int sgemm_config_lds_bytes(const sgemm_config *cfg); /* LDS the variant will declare       */
 int sgemm_config_default(int M, int N, int K, int layout, sgemm_config *out);
+/* How cfg's split K applies to a problem with this K: *parts (may be null) receives the number
+ * of workgroups per tile that will really be launched (sk limited to the number of K slabs,
+ * no empty parts), *k_chunk (may be null) the k range of each part, a multiple of kwg (K itself
+ * when there is one part).  Returns the bytes of device workspace a call with this
+ * configuration uses for an M x N result: parts * M * N * 4, or 0 when parts == 1. */
+long long sgemm_config_workspace_bytes(const sgemm_config *cfg, int M, int N, int K, int *parts,
+                                       int *k_chunk);
 
 /* ---- kernel generator --------------------------------------------------------------- */
 /* [host] Directory of the on-disk code-object cache (default: "kcache" beside the library,
  * or $SGEMM_TUNED_CACHE_DIR). */
 int sgemm_kernel_cache_dir(const char *path);
 /* [host] Compile (or fetch from the cache) the variant for cfg/layout; edge = 1 builds the
- * bounds-guarded form.  Needs no GPU.  info may be null. */
+ * bounds-guarded form.  cfg->sk > 1 selects the build that split-K launches use (one build
+ * for every sk > 1: the split itself is a launch parameter).  Needs no GPU.  info may be null. */
 int sgemm_kernel_compile(const sgemm_config *cfg, int layout, int edge, sgemm_kernel_info *info);
 /* [host] The -D macro string the variant is compiled with, NUL-terminated into buf. */
 int sgemm_kernel_macros(const sgemm_config *cfg, int layout, int edge, char *buf, int cap);

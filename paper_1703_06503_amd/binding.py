@@ -88,6 +88,7 @@ EXPORTS = (
     "tune", "tune_ex", "tune_replay", "sgemm_space_size", "sgemm_space_raw_size",
     "sgemm_space_get", "sgemm_space_find", "sgemm_space_dims", "sgemm_space_values",
     "sgemm_config_check", "sgemm_config_lds_bytes", "sgemm_config_default",
+    "sgemm_config_workspace_bytes",
     "sgemm_kernel_cache_dir", "sgemm_kernel_compile", "sgemm_kernel_macros", "sgemm_config_get",
     "sgemm_config_set", "sgemm_config_select", "sgemm_cache_load", "sgemm_cache_save",
     "sgemm_cache_clear", "sgemm_cache_count", "sgemm_device_peak", "sgemm_status_string",
@@ -281,6 +282,17 @@ def sgemm_config_check(cfg):
 
 def sgemm_config_lds_bytes(cfg):
     return _check(lib().sgemm_config_lds_bytes(ctypes.byref(cfg)), "sgemm_config_lds_bytes")
+
+
+def sgemm_config_workspace_bytes(cfg, M, N, K):
+    """(bytes of device workspace, parts, k_chunk) of a call with cfg on an M x N x K problem."""
+    parts, chunk = ctypes.c_int(), ctypes.c_int()
+    f = lib().sgemm_config_workspace_bytes
+    f.restype = ctypes.c_longlong
+    n = f(ctypes.byref(cfg), M, N, K, ctypes.byref(parts), ctypes.byref(chunk))
+    if n < 0:
+        raise SgemmError(int(n), "sgemm_config_workspace_bytes")
+    return int(n), parts.value, chunk.value
 
 
 def sgemm_config_default(M, N, K, layout=0):

@@ -44,8 +44,12 @@ def build(verbose: bool = False) -> str:
               f"-I{ROCM}/include", f'-DSGEMM_KERNEL_SOURCE_PATH="{kernel_src}"',
               "-c", os.path.join(CSRC, s), "-o", o], verbose)
         objs.append(o)
-    _run([HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB, *objs,
+    # link beside the target and rename over it: a process that has the old library mapped
+    # (a precompile pool, a running search) keeps its copy intact
+    tmp = LIB + f".{os.getpid()}.tmp"
+    _run([HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", tmp, *objs,
           f"-L{ROCM}/lib", "-lhiprtc", "-ldl", f"-Wl,-rpath,{ROCM}/lib"], verbose)
+    os.replace(tmp, LIB)
     return LIB
 
 

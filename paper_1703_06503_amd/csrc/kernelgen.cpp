@@ -122,10 +122,10 @@ std::string VariantKey::macros() const {
     char buf[512];
     std::snprintf(buf, sizeof buf,
                   "-DMWG=%d -DNWG=%d -DKWG=%d -DMDIMC=%d -DNDIMC=%d -DVWM=%d -DVWN=%d -DSA=%d "
-                  "-DSB=%d -DPAD=%d -DKWI=%d -DMFMA=%d -DGRP=%d -DNS=%d -DTRA=%d -DTRB=%d -DEDGE=%d",
+                  "-DSB=%d -DPAD=%d -DKWI=%d -DMFMA=%d -DGRP=%d -DNS=%d -DTRA=%d -DTRB=%d -DEDGE=%d -DSPLITK=%d",
                   cfg.mwg, cfg.nwg, cfg.kwg, cfg.mdimc, cfg.ndimc, cfg.vwm, cfg.vwn, cfg.sa, cfg.sb,
                   cfg.pad, cfg.kwi, cfg.mfma, cfg.grp, cfg.ns > 0 ? cfg.ns : 2, layout & 1,
-                  (layout >> 1) & 1, edge ? 1 : 0);
+                  (layout >> 1) & 1, edge ? 1 : 0, splitk ? 1 : 0);
     return buf;
 }
 

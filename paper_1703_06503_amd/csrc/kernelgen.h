@@ -19,6 +19,7 @@ struct VariantKey {
     sgemm_config cfg;
     int layout;
     int edge;
+    int splitk = 0; // 1 = the build that split-K launches use (cfg.sk itself is not compiled in)
     std::string macros() const; // "-DMWG=.. -DNWG=.. ..." in a fixed order
 };
 

@@ -160,12 +160,14 @@ VariantKey resolve_variant(const sgemm_config &cfg, int M, int N, int K, const f
     if (key.cfg.vwn > 1 && ((vwn_loads_b && !aligned_for(B, ldb, key.cfg.vwn)) || (vwn_stores_c && !c_ok)))
         key.cfg.vwn = 1;
     key.edge = (M % cfg.mwg || N % cfg.nwg || K % cfg.kwg) ? 1 : 0;
+    key.splitk = splits_k(cfg, K) ? 1 : 0;
     if (key.cfg.ns == 0) key.cfg.ns = 2;
-    // a guarded LDS-direct load replaces whole vectors by zeros, so a stored row must not end
-    // inside one; narrower loads mean more of them, which may not leave room for 3 or 4 buffers
+    // a guarded tile load clamps or zeroes whole vectors, so a stored row must not end inside
+    // one; narrower LDS-direct loads mean more of them, which may not leave room for 3 or 4
+    // buffers
     if (key.edge) {
-        if (key.cfg.sa == 2 && ((layout & 1) ? M : K) % key.cfg.vwm) key.cfg.vwm = 1;
-        if (key.cfg.sb == 2 && ((layout & 2) ? K : N) % key.cfg.vwn) key.cfg.vwn = 1;
+        if (key.cfg.sa && ((layout & 1) ? M : K) % key.cfg.vwm) key.cfg.vwm = 1;
+        if (key.cfg.sb && ((layout & 2) ? K : N) % key.cfg.vwn) key.cfg.vwn = 1;
     }
     while (key.cfg.ns > 2 && (key.cfg.ns - 2) * direct_loads_per_slab(key.cfg) > kMaxLoadsInFlight)
         --key.cfg.ns;
@@ -178,13 +180,17 @@ VariantKey resolve_variant(const sgemm_config &cfg, int M, int N, int K, const f
     return key;
 }
 
-// Device workspace for split-K partial planes: one per process, grown on demand and kept.
-// Calls that overlap in time on different streams and both split K would share it, so such
+// Device workspace for split K: the partial planes and one arrival counter per tile of C.
+// One per process, grown on demand and kept.  The counters are zeroed when allocated and every
+// launch leaves them at zero again (the last part of a tile resets its counter).  Calls that
+// overlap in time on different streams and both split K would share the workspace, so such
 // calls must be ordered by the caller (the same rule as for any single-workspace library).
 float *g_workspace = nullptr;
 size_t g_workspace_floats = 0;
+unsigned int *g_counters = nullptr;
+size_t g_counters_count = 0;
 
-int workspace_for(size_t floats, float **out) {
+int workspace_for(size_t floats, size_t tiles, float **planes, unsigned int **counters) {
     std::lock_guard<std::mutex> lock(g_mu);
     if (floats > g_workspace_floats) {
         // hipFree waits for the device, so no kernel is still using the old buffer
@@ -201,8 +207,35 @@ int workspace_for(size_t floats, float **out) {
         g_workspace = static_cast<float *>(p);
         g_workspace_floats = want;
     }
-    *out = g_workspace;
+    if (tiles > g_counters_count) {
+        if (g_counters) (void)hipFree(g_counters);
+        g_counters = nullptr;
+        g_counters_count = 0;
+        void *p = nullptr;
+        const size_t want = std::max(tiles, (size_t)65536);
+        hipError_t e = hipMalloc(&p, want * sizeof(unsigned int));
+        if (e == hipSuccess) e = hipMemset(p, 0, want * sizeof(unsigned int));
+        if (e != hipSuccess) {
+            set_error(std::string("hipMalloc of the split-K counters: ") + hipGetErrorString(e));
+            if (p) (void)hipFree(p);
+            return SGEMM_E_LAUNCH;
+        }
+        g_counters = static_cast<unsigned int *>(p);
+        g_counters_count = want;
+    }
+    *planes = g_workspace;
+    *counters = g_counters;
     return SGEMM_OK;
+}
+
+// SGEMM_TUNED_SPLITK=two_pass makes split-K launches leave the planes to a separate reduction
+// kernel instead of to the last workgroup of each tile (same result bit for bit).
+bool split_two_pass() {
+    static const bool v = [] {
+        const char *e = std::getenv("SGEMM_TUNED_SPLITK");
+        return e && std::strcmp(e, "two_pass") == 0;
+    }();
+    return v;
 }
 
 // How a configuration's SK is applied to a problem: `parts` workgroups per tile, each summing
@@ -231,29 +264,25 @@ int launch_loaded(hipStream_t s, const LoadedKernel &k, const sgemm_config &cfg,
     if (wgs > 0x7fffffffll) return SGEMM_E_BADARG;
     const SplitPlan plan = plan_split(cfg, K);
     int k_chunk = plan.k_chunk;
-    long long split_stride = 0;
-    float *out = C;
-    int ldo = ldc;
-    float a = alpha, b = beta;
+    float *planes = nullptr;
+    unsigned int *counters = nullptr;
     if (plan.parts > 1) {
-        // every part writes its raw sum into its own plane; the reduction applies alpha, beta
-        const int rc = workspace_for((size_t)plan.parts * (size_t)M * (size_t)N, &out);
+        // every part writes its raw sum into its own plane; the last part of a tile (or the
+        // reduction kernel) adds them up and applies alpha and beta
+        const int rc = workspace_for((size_t)plan.parts * (size_t)M * (size_t)N, (size_t)wgs, &planes, &counters);
         if (rc != SGEMM_OK) return rc;
-        split_stride = (long long)M * N;
-        ldo = N;
-        a = 1.0f;
-        b = 0.0f;
+        if (split_two_pass()) counters = nullptr;
     }
-    void *args[] = {&M, &N, &K, &a, &A, &lda, &B, &ldb, &b, &out, &ldo, &tiles_m, &tiles_n,
-                    &k_chunk, &split_stride};
+    void *args[] = {&M, &N, &K, &alpha, &A, &lda, &B, &ldb, &beta, &C, &ldc, &tiles_m, &tiles_n,
+                    &k_chunk, &planes, &counters};
     const hipError_t e = hipModuleLaunchKernel(k.fn, (unsigned)wgs, (unsigned)plan.parts, 1,
                                                (unsigned)k.threads, 1, 1, 0, s, args, nullptr);
     if (e != hipSuccess) {
         set_error(std::string("hipModuleLaunchKernel: ") + hipGetErrorString(e));
         return SGEMM_E_LAUNCH;
     }
-    if (plan.parts > 1) {
-        const hipError_t r = sgemm_util::launch_splitk_reduce(s, M, N, plan.parts, out, (size_t)split_stride,
+    if (plan.parts > 1 && counters == nullptr) {
+        const hipError_t r = sgemm_util::launch_splitk_reduce(s, M, N, plan.parts, planes, (size_t)M * (size_t)N,
                                                               alpha, beta, C, ldc);
         if (r != hipSuccess) {
             set_error(std::string("split-K reduction: ") + hipGetErrorString(r));
@@ -468,6 +497,16 @@ int sgemm_config_lds_bytes(const sgemm_config *cfg) {
     return lds_bytes(*cfg);
 }
 
+long long sgemm_config_workspace_bytes(const sgemm_config *cfg, int M, int N, int K, int *parts,
+                                       int *k_chunk) {
+    if (!cfg || M < 0 || N < 0 || K < 0) return SGEMM_E_BADARG;
+    if (violates(*cfg)) return SGEMM_E_INVALID;
+    const SplitPlan plan = plan_split(*cfg, K);
+    if (parts) *parts = plan.parts;
+    if (k_chunk) *k_chunk = plan.k_chunk;
+    return plan.parts > 1 ? (long long)plan.parts * M * N * 4 : 0;
+}
+
 int sgemm_config_default(int M, int N, int K, int layout, sgemm_config *out) {
     if (!out || M < 0 || N < 0 || K < 0 || layout < 0 || layout > 3) return SGEMM_E_BADARG;
     *out = default_config(M, N, K);
@@ -487,7 +526,7 @@ int sgemm_kernel_compile(const sgemm_config *cfg, int layout, int edge, sgemm_ke
     if (violates(*cfg)) return SGEMM_E_INVALID;
     CodeObject co;
     std::string log;
-    const int rc = get_code_object(VariantKey{*cfg, layout, edge ? 1 : 0}, &co, &log);
+    const int rc = get_code_object(VariantKey{*cfg, layout, edge ? 1 : 0, cfg->sk > 1 ? 1 : 0}, &co, &log);
     if (rc != SGEMM_OK) set_error(log);
     if (info) *info = co.info;
     return rc;
@@ -495,7 +534,7 @@ int sgemm_kernel_compile(const sgemm_config *cfg, int layout, int edge, sgemm_ke
 
 int sgemm_kernel_macros(const sgemm_config *cfg, int layout, int edge, char *buf, int cap) {
     if (!cfg || !buf || cap <= 0) return SGEMM_E_BADARG;
-    const std::string m = VariantKey{*cfg, layout, edge ? 1 : 0}.macros();
+    const std::string m = VariantKey{*cfg, layout, edge ? 1 : 0, cfg->sk > 1 ? 1 : 0}.macros();
     if ((int)m.size() + 1 > cap) return SGEMM_E_BADARG;
     std::memcpy(buf, m.c_str(), m.size() + 1);
     return SGEMM_OK;

@@ -83,15 +83,48 @@ def test_kernel_generator_compiles_without_a_gpu(tmp_path):
         assert "-DSA=2" in b.sgemm_kernel_macros(direct, 0, 0)
         assert "-DNS=3" in b.sgemm_kernel_macros(direct, 0, 0)
         assert b.sgemm_kernel_compile(direct, 1, 1).scratch_bytes == 0      # guarded form
-        # split K is applied at launch: it is not part of what is compiled
-        split = b.make_config(64, 64, 16, 8, 8, 4, 4, 1, 1, 1, 8, 1, 0, 8)
-        assert b.sgemm_kernel_macros(split, 0, 0) == b.sgemm_kernel_macros(cfg, 0, 0)
+        # the split itself is applied at launch: every sk > 1 shares one build, which differs
+        # from the unsplit one only by the code that handles the partial planes
+        split8 = b.make_config(64, 64, 16, 8, 8, 4, 4, 1, 1, 1, 8, 1, 0, 8)
+        split3 = b.make_config(64, 64, 16, 8, 8, 4, 4, 1, 1, 1, 8, 1, 0, 3)
+        assert b.sgemm_kernel_macros(split8, 0, 0) == b.sgemm_kernel_macros(split3, 0, 0)
+        assert "-DSPLITK=1" in b.sgemm_kernel_macros(split8, 0, 0)
+        assert (b.sgemm_kernel_macros(split8, 0, 0).replace("-DSPLITK=1", "-DSPLITK=0")
+                == b.sgemm_kernel_macros(cfg, 0, 0))
+        assert b.sgemm_kernel_compile(split8, 0, 1).scratch_bytes == 0
         bad = b.make_config(64, 64, 16, 8, 8, 4, 4, 0, 1, 1, 8, 1, 0)   # VWM without staging A
         with pytest.raises(b.SgemmError) as e:
             b.sgemm_kernel_compile(bad, 0, 0)
         assert e.value.status == b.E_INVALID
     finally:
         b.sgemm_kernel_cache_dir(os.path.join(os.path.dirname(b.LIB_PATH), "kcache"))
+
+
+def test_split_k_plan_and_workspace_size():
+    """sk workgroups per tile, limited to the number of K slabs, parts of whole slabs, none
+    empty; the workspace holds one M x N plane per part."""
+    cfg = b.make_config(64, 64, 32, 16, 16, 4, 4, 1, 1, 1, 8, 1, 0, 4)
+    assert b.sgemm_config_workspace_bytes(cfg, 100, 50, 4096) == (4 * 100 * 50 * 4, 4, 1024)
+    assert b.sgemm_config_workspace_bytes(cfg, 100, 50, 100) == (4 * 100 * 50 * 4, 4, 32)   # 4 slabs
+    assert b.sgemm_config_workspace_bytes(cfg, 100, 50, 33) == (2 * 100 * 50 * 4, 2, 32)    # 2 slabs
+    assert b.sgemm_config_workspace_bytes(cfg, 100, 50, 32) == (0, 1, 32)                   # 1 slab
+    # 9 slabs over 4 parts: chunks of 3 slabs leave nothing for a fourth part
+    assert b.sgemm_config_workspace_bytes(cfg, 8, 8, 9 * 32) == (3 * 8 * 8 * 4, 3, 96)
+    # 10 slabs over 4 parts: 3, 3, 3, 1
+    assert b.sgemm_config_workspace_bytes(cfg, 8, 8, 10 * 32) == (4 * 8 * 8 * 4, 4, 96)
+    for K in range(1, 700, 13):
+        for sk in (1, 2, 3, 4, 6, 8, 12, 16):
+            c = b.make_config(64, 64, 32, 16, 16, 4, 4, 1, 1, 1, 8, 1, 0, sk)
+            nbytes, parts, chunk = b.sgemm_config_workspace_bytes(c, 3, 5, K)
+            slabs = -(-K // 32)
+            assert 1 <= parts <= min(sk, slabs)
+            if parts > 1:
+                assert chunk % 32 == 0 and (parts - 1) * chunk < K <= parts * chunk
+                assert nbytes == parts * 3 * 5 * 4
+            else:
+                assert chunk == K and nbytes == 0
+    unsplit = b.make_config(64, 64, 32, 16, 16, 4, 4, 1, 1, 1, 8, 1, 0)
+    assert b.sgemm_config_workspace_bytes(unsplit, 100, 50, 4096) == (0, 1, 4096)
 
 
 def test_per_shape_cache_roundtrip(tmp_path):
