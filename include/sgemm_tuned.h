@@ -136,7 +136,11 @@ typedef struct tune_opts {
     const float *C0;    /* optional DEVICE copy of the initial C (needed when beta != 0)  */
     int lda, ldb, ldc;
     const char *log_path; /* optional HOST path: one JSON line appended per evaluation    */
-    int reserved[8];
+    int warm_start;     /* 1 = annealing (and particle 0 of the swarm) starts at the
+                           configuration the per-shape cache would use for this shape, if it
+                           lies in the searched space, instead of at a random one; -(i+1) =
+                           start at configuration i of the space (tune_replay too)           */
+    int reserved[7];
 } tune_opts;
 
 typedef struct tune_result {

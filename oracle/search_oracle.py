@@ -16,7 +16,8 @@ Readings where the paper is silent (the library documents the same ones):
   - budget = number of DISTINCT configurations whose cost is asked for; a revisit is free;
     a search also stops after 20*budget moves.
   - random search: the first `budget` steps of a Fisher-Yates shuffle of 0..n-1.
-  - annealing: start s = below(n).  Neighbours of s = valid configurations differing from s
+  - annealing: start s = below(n), or a given configuration (then no draw is made: a search
+    may be continued from a known good point).  Neighbours of s = valid configurations differing from s
     in exactly one parameter, ordered by parameter then by position in its value list; s' is
     drawn uniformly from them (from the whole space if there are none).  The paper's formula
     has a single T but says the temperature decreases over the search: T_i = T * (1 - e/budget)
@@ -24,8 +25,8 @@ Readings where the paper is silent (the library documents the same ones):
     compared in percent of the best time found so far (scale-free; raw milliseconds optional):
     P = 1 if t' < t, else exp(-(t' - t) / T_i).  A failed s' is never accepted; a failed s is
     always left.
-  - particle swarm: positions start at below(n) for each of the S particles in turn and are
-    evaluated; then particles move one at a time, round robin.  For each dimension d one
+  - particle swarm: positions start at below(n) for each of the S particles in turn (particle
+    0 at the given start configuration, if there is one) and are evaluated; then particles move one at a time, round robin.  For each dimension d one
     uniform() decides: < alpha: epsilon_d = values[d][below(len)], < alpha+beta: p_i,d,
     < alpha+beta+gamma: g_d, else x_i,d.  An invalid mix is redrawn up to 10 times, then the
     particle jumps to below(n).  p_i and g are updated right after every evaluation.
@@ -132,13 +133,13 @@ def neighbours(configs, values, index_of, s):
     return out
 
 
-def simulated_annealing(configs, values, t, budget, seed, T=4.0, raw_ms=False):
+def simulated_annealing(configs, values, t, budget, seed, T=4.0, raw_ms=False, start=None):
     n = len(configs)
     budget = max(1, min(budget, n))
     index_of = {c: i for i, c in enumerate(configs)}
     costs = _Costs(t, budget)
     rng = SplitMix64(seed)
-    s = rng.below(n)
+    s = rng.below(n) if start is None else start
     t_s = costs(s)
     trace = [s]
     moves = 0
@@ -163,7 +164,8 @@ def simulated_annealing(configs, values, t, budget, seed, T=4.0, raw_ms=False):
     return costs.result(trace=trace)
 
 
-def particle_swarm(configs, values, t, budget, seed, S=3, alpha=0.4, beta=0.0, gamma=0.4):
+def particle_swarm(configs, values, t, budget, seed, S=3, alpha=0.4, beta=0.0, gamma=0.4,
+                   start=None):
     n = len(configs)
     budget = max(1, min(budget, n))
     index_of = {c: i for i, c in enumerate(configs)}
@@ -173,7 +175,7 @@ def particle_swarm(configs, values, t, budget, seed, S=3, alpha=0.4, beta=0.0, g
     g, g_cost = -1, math.inf
     positions = []                      # (particle, position) after every move
     for i in range(S):
-        xi = rng.below(n)
+        xi = start if (i == 0 and start is not None) else rng.below(n)
         if not costs.affordable(xi):
             return costs.result(positions=positions)
         c = costs(xi)

@@ -71,7 +71,7 @@ class tune_opts(ctypes.Structure):
                 ("A", ctypes.c_void_p), ("B", ctypes.c_void_p), ("C", ctypes.c_void_p),
                 ("C0", ctypes.c_void_p), ("lda", ctypes.c_int), ("ldb", ctypes.c_int),
                 ("ldc", ctypes.c_int), ("log_path", ctypes.c_char_p),
-                ("reserved", ctypes.c_int * 8)]
+                ("warm_start", ctypes.c_int), ("reserved", ctypes.c_int * 7)]
 
 
 class tune_result(ctypes.Structure):

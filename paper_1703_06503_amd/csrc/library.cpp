@@ -345,6 +345,7 @@ StrategyParams params_from(const tune_opts *o) {
         p.pso_alpha = o->pso_alpha; p.pso_beta = o->pso_beta; p.pso_gamma = o->pso_gamma;
     }
     if (o->random_fraction > 0) p.random_fraction = o->random_fraction;
+    if (o->warm_start < 0) p.start_index = -o->warm_start - 1;
     return p;
 }
 
@@ -795,7 +796,14 @@ int tune_ex(int M, int N, int K, int layout, float alpha, float beta, int strate
         return ms;
     };
 
-    const SearchResult r = run_search(*space, strategy, budget, seed, params_from(opts), evaluate);
+    StrategyParams sp = params_from(opts);
+    if (opts && opts->warm_start > 0) {
+        sgemm_config cached;
+        std::lock_guard<std::mutex> lock(g_mu);
+        select_config_locked(M, N, K, layout, &cached);
+        sp.start_index = space->find(to_point(cached)); // -1 when it is not in this space
+    }
+    const SearchResult r = run_search(*space, strategy, budget, seed, sp, evaluate);
     if (logf) std::fclose(logf);
     (void)hipStreamSynchronize(s);
     fill_result(*space, r, flops, out);

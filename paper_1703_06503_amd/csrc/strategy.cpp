@@ -82,7 +82,7 @@ void random_search(Evaluator &ev, int n, Rng &rng) {
 
 void annealing(Evaluator &ev, const Space &space, Rng &rng, const StrategyParams &p) {
     const int n = (int)space.configs.size();
-    int cur = (int)rng.below((uint64_t)n);
+    int cur = (p.start_index >= 0 && p.start_index < n) ? p.start_index : (int)rng.below((uint64_t)n);
     double t = ev.get(cur);
     const long long max_steps = 20ll * ev.budget;
     for (long long step = 0; step < max_steps && ev.res.evaluations < ev.budget; ++step) {
@@ -114,7 +114,8 @@ void particle_swarm(Evaluator &ev, const Space &space, Rng &rng, const StrategyP
     int g = -1;
     double g_cost = kInf;
     for (int i = 0; i < S; ++i) {
-        x[i] = (int)rng.below((uint64_t)n);
+        x[i] = (i == 0 && p.start_index >= 0 && p.start_index < n) ? p.start_index
+                                                                   : (int)rng.below((uint64_t)n);
         if (!ev.can_afford(x[i])) return;
         const double c = ev.get(x[i]);
         best[i] = x[i];

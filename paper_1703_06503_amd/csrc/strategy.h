@@ -27,6 +27,8 @@ struct StrategyParams {
     int pso_S = 3;            // swarm size
     double pso_alpha = 0.4, pso_beta = 0.0, pso_gamma = 0.4;
     double random_fraction = 0.0; // random search budget as a fraction when budget <= 0
+    int start_index = -1;     // >= 0: annealing starts here, and so does particle 0 of the
+                              // swarm, instead of at a random configuration (no draw is made)
 };
 
 struct SearchResult {

@@ -29,6 +29,8 @@ def main(argv=None):
     ap.add_argument("--pso-S", type=int, default=0)
     ap.add_argument("--fraction", type=float, default=0.0)
     ap.add_argument("--no-verify", action="store_true")
+    ap.add_argument("--warm-start", action="store_true",
+                    help="start annealing / particle 0 at the configuration cached for the shape")
     ap.add_argument("--log", default=None)
     ap.add_argument("--save", default=None)
     ap.add_argument("--load", default=None, help="best-configuration table to merge first")
@@ -53,6 +55,7 @@ def main(argv=None):
     opts.pso_S = a.pso_S
     opts.random_fraction = a.fraction
     opts.verify_off = 1 if a.no_verify else 0
+    opts.warm_start = 1 if a.warm_start else 0
     opts.A, opts.B, opts.C, opts.C0 = dA.data_ptr(), dB.data_ptr(), dC.data_ptr(), dC0.data_ptr()
     opts.lda, opts.ldb, opts.ldc = A.shape[1], B.shape[1], w.N
     if a.log:

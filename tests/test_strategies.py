@@ -263,6 +263,28 @@ def test_library_pso_matches_oracle(S):
                                                            want["evals_to_best"])
 
 
+def test_library_warm_start_matches_oracle():
+    """A search continued from a given configuration: annealing starts there, the swarm's
+    particle 0 starts there, and no random draw is spent on that start."""
+    cfgs = SPACES[sp.SPACE_FULL]
+    vals = sp.VALUES[sp.SPACE_FULL]
+    t = synthetic_costs(cfgs, 60)
+    for start in (0, 1234, len(cfgs) - 1):
+        ev, res, visited = b.tune_replay(b.SPACE_FULL, t, b.STRATEGY_ANNEALING, 60, 3,
+                                         _opts(warm_start=-(start + 1)))
+        want = so.simulated_annealing(cfgs, vals, t, 60, 3, start=start)
+        assert visited[0] == start and visited == want["visited"]
+        ev, res, visited = b.tune_replay(b.SPACE_FULL, t, b.STRATEGY_PSO, 60, 3,
+                                         _opts(pso_S=3, warm_start=-(start + 1)))
+        want = so.particle_swarm(cfgs, vals, t, 60, 3, S=3, start=start)
+        assert visited[0] == start and visited == want["visited"]
+    # a start that is the optimum is never lost
+    tt = np.asarray(t, dtype=np.float64)
+    best = int(np.argmin(np.where(np.isfinite(tt) & (tt > 0), tt, np.inf)))
+    _, res, _ = b.tune_replay(b.SPACE_FULL, t, b.STRATEGY_ANNEALING, 40, 9, _opts(warm_start=-(best + 1)))
+    assert res.best_index == best
+
+
 def test_library_small_space_all_strategies_and_edge_budgets():
     cfgs = SPACES[sp.SPACE_SMALL]
     vals = sp.VALUES[sp.SPACE_SMALL]
