@@ -228,12 +228,13 @@ int workspace_for(size_t floats, size_t tiles, float **planes, unsigned int **co
     return SGEMM_OK;
 }
 
-// SGEMM_TUNED_SPLITK=two_pass makes split-K launches leave the planes to a separate reduction
-// kernel instead of to the last workgroup of each tile (same result bit for bit).
+// How the planes of a split-K launch are added up: by default a second kernel does it;
+// SGEMM_TUNED_SPLITK=fused lets the last workgroup of each tile do it inside the GEMM launch
+// (same result bit for bit; measured equally fast, so the simpler way is the default).
 bool split_two_pass() {
     static const bool v = [] {
         const char *e = std::getenv("SGEMM_TUNED_SPLITK");
-        return e && std::strcmp(e, "two_pass") == 0;
+        return !(e && std::strcmp(e, "fused") == 0);
     }();
     return v;
 }
