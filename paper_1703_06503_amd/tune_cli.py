@@ -34,6 +34,10 @@ def main(argv=None):
     ap.add_argument("--log", default=None)
     ap.add_argument("--save", default=None)
     ap.add_argument("--load", default=None, help="best-configuration table to merge first")
+    ap.add_argument("--start-config", default=None,
+                    help="comma-separated configuration (field order of sgemm_config) to put into "
+                         "the per-shape cache for this workload before the search; with "
+                         "--warm-start the search begins there")
     a = ap.parse_args(argv)
 
     import torch
@@ -46,6 +50,9 @@ def main(argv=None):
     dC = dC0.clone()
     if a.load:
         b.sgemm_cache_load(a.load)
+    if a.start_config:
+        start = b.make_config(*[int(x) for x in a.start_config.split(",")])
+        b.sgemm_config_set(w.M, w.N, w.K, w.layout, start, 0.0)   # time unknown: any result replaces it
     opts = b.tune_opts()
     opts.space = SPACES[a.space]
     opts.reps = a.reps
