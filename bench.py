@@ -116,6 +116,7 @@ def main():
         opts = b.tune_opts()
         opts.space = b.SPACE_MFMA
         opts.pso_S = 6
+        opts.warm_start = 1        # particle 0 starts at the cached configuration
         opts.A, opts.B, opts.C, opts.C0 = dA.data_ptr(), dB.data_ptr(), dC.data_ptr(), dC0.data_ptr()
         opts.lda, opts.ldb, opts.ldc = lda, ldb, ldc
         t0 = time.perf_counter()

@@ -313,3 +313,120 @@ def test_non_tile_multiple_sizes_full_compare(workload):
         gu.check_against_oracle(got, A, B, C, w.alpha, w.beta, w.layout, ref, what=f"{workload} {cfg}")
     got = gu.run_gpu(None, A, B, C, w.alpha, w.beta, w.layout, entry="tuned")
     gu.check_against_oracle(got, A, B, C, w.alpha, w.beta, w.layout, ref, what=f"{workload} tuned")
+
+
+# ---- the tuner and the dispatch entry points on the device ---------------------------------
+
+def _restore_cache():
+    """Back to what a fresh process starts with: the committed table of tuned configurations."""
+    import os
+    b.sgemm_cache_clear()
+    table = os.path.join(os.path.dirname(b.LIB_PATH), "..", "tuned_configs.txt")
+    if os.path.exists(table):
+        b.sgemm_cache_load(table)
+
+
+def _device_operands(workload):
+    import torch
+    w = synth.WORKLOADS[workload]
+    A, B, C = synth.make_workload(w)
+    dA, dB, dC0 = (torch.from_numpy(x).cuda() for x in (A, B, C))
+    return w, (A, B, C), dA, dB, dC0.clone(), dC0
+
+
+def test_tune_ex_full_search_of_the_small_space(tmp_path):
+    """Benchmark configuration 1 end to end: 16 variants compiled, verified against the device
+    reference kernel, timed; the winner lands in the per-shape cache and sgemm_tuned() then
+    agrees with the oracle."""
+    import json
+    import torch
+    w, (A, B, C), dA, dB, dC, dC0 = _device_operands("cfg1_256")
+    log = tmp_path / "evals.jsonl"
+    opts = b.tune_opts()
+    opts.space = b.SPACE_SMALL
+    opts.A, opts.B, opts.C, opts.C0 = dA.data_ptr(), dB.data_ptr(), dC.data_ptr(), dC0.data_ptr()
+    opts.lda, opts.ldb, opts.ldc = w.K, w.N, w.N
+    opts.log_path = str(log).encode()
+    b.sgemm_cache_clear()
+    try:
+        evals, res = b.tune_ex(w.M, w.N, w.K, w.layout, w.alpha, w.beta, b.STRATEGY_FULL, 0, 0, opts)
+        assert evals == 16 and res.space_size == 16 and res.failed == 0
+        assert 0 <= res.best_index < 16 and res.best_ms > 0 and res.best_gflops > 0
+        assert res.best.as_tuple() == b.sgemm_space_get(b.SPACE_SMALL, res.best_index).as_tuple()
+        rows = [json.loads(line) for line in log.read_text().splitlines()]
+        assert [r["index"] for r in rows] == list(range(16))
+        assert all(r["status"].startswith("ok") and r["scratch"] == 0 for r in rows)
+        assert min(r["ms"] for r in rows) == pytest.approx(res.best_ms, rel=1e-4)   # log prints 6 digits
+        assert b.sgemm_config_get(w.M, w.N, w.K, w.layout).as_tuple() == res.best.as_tuple()
+        dC.copy_(dC0)
+        b.sgemm_tuned_on(None, w.M, w.N, w.K, w.alpha, dA, w.K, dB, w.N, w.beta, dC, w.N, w.layout)
+        torch.cuda.synchronize()
+        gu.check_against_oracle(dC.cpu().numpy(), A, B, C, w.alpha, w.beta, w.layout)
+    finally:
+        _restore_cache()
+
+
+@pytest.mark.parametrize("strategy", [b.STRATEGY_RANDOM, b.STRATEGY_ANNEALING, b.STRATEGY_PSO])
+def test_tune_ex_budgeted_strategies(strategy):
+    """A budget counts distinct configurations; every one of them is verified on a C restored
+    from C0 (with beta != 0 the timed repetitions then keep updating C); the caller's C0 is
+    never touched."""
+    import torch
+    M, N, K = 192, 160, 96
+    A, B, C = synth.make_inputs(M, N, K, 0, seed=71)
+    dA, dB, dC0 = (torch.from_numpy(x).cuda() for x in (A, B, C))
+    dC = dC0.clone()
+    opts = b.tune_opts()
+    opts.space = b.SPACE_SMALL
+    opts.A, opts.B, opts.C, opts.C0 = dA.data_ptr(), dB.data_ptr(), dC.data_ptr(), dC0.data_ptr()
+    opts.lda, opts.ldb, opts.ldc = K, N, N
+    opts.reps, opts.warmup_ms = 3, -1.0
+    b.sgemm_cache_clear()
+    try:
+        evals, res = b.tune_ex(M, N, K, 0, 1.5, 0.5, strategy, 6, 3, opts)
+        assert 1 <= evals <= 6 and res.failed == 0 and res.best_index >= 0
+        assert torch.equal(dC0.cpu(), torch.from_numpy(C))
+    finally:
+        _restore_cache()
+
+
+def test_tune_simple_entry_point_and_dispatch_fallback():
+    """tune(M,N,K,strategy,budget) on library-owned synthetic operands; afterwards a nearby
+    untuned shape is served by the tuned shape's configuration."""
+    import torch
+    b.sgemm_cache_clear()
+    try:
+        evals = b.tune(256, 256, 128, b.STRATEGY_RANDOM, 3)
+        assert 1 <= evals <= 3
+        tuned = b.sgemm_config_get(256, 256, 128, 0)
+        assert tuned is not None and b.sgemm_config_check(tuned) == 0
+        assert b.sgemm_config_select(250, 260, 128, 0).as_tuple() == tuned.as_tuple()
+        A, B, C = synth.make_inputs(250, 260, 128, 0, seed=72)
+        got = gu.run_gpu(None, A, B, C, 1.0, 0.0, 0, entry="tuned")
+        gu.check_against_oracle(got, A, B, C, 1.0, 0.0, 0)
+    finally:
+        _restore_cache()
+
+
+def test_launch_on_a_side_stream_and_on_the_set_stream():
+    import torch
+    cfg = _some_configs()[1]
+    A, B, C = synth.make_inputs(300, 200, 150, 0, seed=73)
+    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    dC = torch.from_numpy(C).cuda()
+    torch.cuda.synchronize()
+    b.sgemm_run_config(side, cfg, 300, 200, 150, 1.0, dA, 150, dB, 200, 1.0, dC, 200, 0)
+    side.synchronize()
+    gu.check_against_oracle(dC.cpu().numpy(), A, B, C, 1.0, 1.0, 0)
+    # sgemm_tuned() launches on the stream given to sgemm_set_stream()
+    dC2 = torch.from_numpy(C).cuda()
+    torch.cuda.synchronize()
+    b.sgemm_set_stream(side)
+    try:
+        b.sgemm_tuned(300, 200, 150, 2.0, dA, 150, dB, 200, 0.0, dC2, 200, 0)
+        side.synchronize()
+    finally:
+        b.sgemm_set_stream(0)
+    gu.check_against_oracle(dC2.cpu().numpy(), A, B, C, 2.0, 0.0, 0)

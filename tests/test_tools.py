@@ -1,0 +1,24 @@
+"""Host-side tools around the library: the table report and the strategy-study helpers."""
+import io
+import contextlib
+
+from paper_1703_06503_amd import report
+
+
+def test_report_reads_old_and_new_tables(tmp_path):
+    t = tmp_path / "table.txt"
+    t.write_text("# M N K layout ms MWG NWG KWG MDIMC NDIMC VWM VWN SA SB PAD KWI MFMA GRP SK NS\n"
+                 "4096 4096 4096 0 1.0 256 256 32 16 16 4 4 1 1 1 8 1 0 1 2\n"
+                 "1024 1024 1024 0 0.05 128 128 16 16 16 4 4 1 1 1 8 1 1\n"          # no SK, NS
+                 "128 4096 4096 1 0.05 64 128 32 16 16 4 4 1 1 0 2 1 1 8 2\n"
+                 "garbage line\n")
+    rows = report.read_table(str(t))
+    assert len(rows) == 3
+    assert rows[1][5] == [128, 128, 16, 16, 16, 4, 4, 1, 1, 1, 8, 1, 1, 1, 2]
+    out = io.StringIO()
+    with contextlib.redirect_stdout(out):
+        assert report.main([str(t), "--peak-tflops", "157.3"]) == 0
+    text = out.getvalue()
+    # 2 * 4096^3 flop in 1 ms = 137 439 GFLOP/s = 87.4 % of 157.3 TFLOP/s
+    assert "| 137439 | 87.4 |" in text
+    assert text.count("\n") == 2 + 3
