@@ -29,14 +29,23 @@ PEAK_FP32_TFLOPS = 157.3   # MI355X published dense FP32 (vector and matrix)
 # and by the variant that was timed; the summaries are under profiles/.  A variant that has
 # not been measured reports null.
 MEASURED_TRAFFIC_BYTES = {
-    ("cfg4_4096", (256, 256, 32, 16, 16, 4, 4, 1, 1, 1, 8, 1, 0, 1)): (295454 * 1.9989 + 65536) * 1024,
+    # profiles/sgemm_tuned_cfg4_4096.txt: 576.59 MiB fetched + 64.00 MiB written
+    ("cfg4_4096", (256, 256, 32, 32, 8, 4, 4, 1, 1, 0, 8, 1, 0, 1, 2)): (576.59 + 64.00) * 2 ** 20,
+    # an earlier winner (16 x 16 threads, padded LDS rows), same tile and tile order
+    ("cfg4_4096", (256, 256, 32, 16, 16, 4, 4, 1, 1, 1, 8, 1, 0, 1, 2)): (295454 * 1.9989 + 65536) * 1024,
+    # profiles/sgemm_tuned_cfg1_256.txt, sgemm_tuned_cfg5_*.txt (GEMM launch + plane reduction)
+    ("cfg1_256", (64, 32, 32, 32, 8, 4, 1, 1, 1, 0, 8, 2, 1, 1, 2)): (2.30 + 0.25) * 2 ** 20,
+    ("cfg5_128x4096x4096", (64, 128, 32, 16, 16, 4, 4, 1, 1, 0, 2, 1, 1, 8, 2)):
+        (80.07 + 16.00 + 16.03 + 2.00) * 2 ** 20,
+    ("cfg5_4096x64x9216", (128, 64, 64, 32, 16, 4, 4, 1, 1, 0, 2, 1, 0, 8, 2)):
+        (161.99 + 8.00 + 8.03 + 1.00) * 2 ** 20,
 }
 
 
 def config_key(cfg):
     d = cfg.as_dict()
     return tuple(d[k] for k in ("mwg", "nwg", "kwg", "mdimc", "ndimc", "vwm", "vwn", "sa", "sb",
-                                "pad", "kwi", "mfma", "grp", "sk"))
+                                "pad", "kwi", "mfma", "grp", "sk", "ns"))
 
 
 def cpu_baseline(w, A, B, C, target_seconds=12.0):
