@@ -93,16 +93,42 @@ void autoload_locked() {
     load_cache_file_locked(p.c_str());
 }
 
-// Built-in fallback when nothing has been tuned: an MFMA variant sized to the problem.
+// Built-in fallback when nothing has been tuned for the storage layout: a matrix-core variant
+// whose tile is chosen the way the tuned shapes turned out - the largest tile whose grid still
+// fills the 256 CUs in whole rounds, weighted by how efficient tiles of that size measured, and
+// split K when even small tiles leave most CUs idle and K is long.
 sgemm_config default_config(int M, int N, int K) {
-    (void)K;
+    struct Cand { int edge, dim, mfma; double eff; };
+    static const Cand cands[] = {{256, 16, 1, 0.92}, {192, 16, 1, 0.88}, {128, 16, 1, 0.85},
+                                 {96, 16, 2, 0.75},  {64, 16, 2, 0.65},  {32, 8, 1, 0.40}};
+    const double cus = 256.0;
+    const Cand *best = &cands[5];
+    double best_score = -1.0;
+    int best_sk = 1;
+    const long long slabs = (K + 31) / 32;
+    for (const Cand &c : cands) {
+        const long long tiles = (long long)((M + c.edge - 1) / c.edge) * ((N + c.edge - 1) / c.edge);
+        if (tiles <= 0) continue;
+        // split K when the tiles alone leave at least half of the CUs idle and K is long
+        // enough for 8 slabs per part; the plane traffic costs about 15 %
+        long long sk = 1;
+        if (tiles * 2 <= (long long)cus && K >= 2048) {
+            sk = std::min<long long>(std::min<long long>((long long)cus / tiles, slabs / 8), 16);
+            if (sk < 1) sk = 1;
+        }
+        const double groups = (double)(tiles * sk);
+        const double rounds = std::ceil(groups / cus);
+        // work really done per CU-round, including what the tile grid overhangs the matrix
+        const double useful = ((double)M * N) / ((double)tiles * c.edge * c.edge);
+        const double score = c.eff * useful * groups / (rounds * cus) * (sk > 1 ? 0.85 : 1.0);
+        if (score > best_score) { best_score = score; best = &c; best_sk = (int)sk; }
+    }
     sgemm_config c{};
-    c.kwg = 16; c.vwm = 4; c.vwn = 4; c.sa = 1; c.sb = 1; c.pad = 1; c.kwi = 8; c.mfma = 1; c.grp = 1;
-    c.sk = 1; c.ns = 2;
-    const long long area = (long long)M * N;
-    if (area >= 2048ll * 2048ll) { c.mwg = 128; c.nwg = 128; c.mdimc = 16; c.ndimc = 16; }
-    else if (area >= 512ll * 512ll) { c.mwg = 64; c.nwg = 64; c.mdimc = 16; c.ndimc = 16; }
-    else { c.mwg = 32; c.nwg = 32; c.mdimc = 8; c.ndimc = 8; c.grp = 0; }
+    c.mwg = c.nwg = best->edge;
+    c.mdimc = c.ndimc = best->dim;
+    c.mfma = best->mfma;
+    c.kwg = 32; c.vwm = 4; c.vwn = 4; c.sa = 1; c.sb = 1; c.pad = 1; c.kwi = 8; c.grp = 1; c.ns = 2;
+    c.sk = best_sk;
     return c;
 }
 

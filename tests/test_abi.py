@@ -127,6 +127,26 @@ def test_split_k_plan_and_workspace_size():
     assert b.sgemm_config_workspace_bytes(unsplit, 100, 50, 4096) == (0, 1, 4096)
 
 
+def test_default_configuration_is_valid_and_sized_to_the_problem():
+    """What sgemm_tuned() falls back on when nothing was tuned for a storage layout."""
+    sizes = [1, 7, 64, 100, 256, 1000, 1536, 3000, 4096, 20000]
+    for M in sizes:
+        for N in sizes:
+            for K in (1, 33, 2048, 9216):
+                c = b.sgemm_config_default(M, N, K)
+                assert b.sgemm_config_check(c) == 0, (M, N, K, c)
+                assert c.mfma in (1, 2) and c.sa == c.sb == 1
+                nbytes, parts, chunk = b.sgemm_config_workspace_bytes(c, M, N, K)
+                assert 1 <= parts <= 16
+    # whole rounds of 256 workgroups where the size allows it
+    assert b.sgemm_config_default(4096, 4096, 4096).mwg == 256
+    assert b.sgemm_config_default(3000, 3000, 3000).mwg == 192        # 16 x 16 tiles
+    assert b.sgemm_config_default(1536, 1536, 1536).mwg == 96         # 16 x 16 tiles
+    # few tiles and a long K: split K
+    assert b.sgemm_config_default(128, 4096, 4096).sk > 1
+    assert b.sgemm_config_default(128, 4096, 64).sk == 1
+
+
 def test_per_shape_cache_roundtrip(tmp_path):
     b.sgemm_cache_clear()
     assert b.sgemm_cache_count() == 0 and b.sgemm_config_get(512, 512, 512, 0) is None

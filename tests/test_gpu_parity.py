@@ -408,6 +408,20 @@ def test_tune_simple_entry_point_and_dispatch_fallback():
         _restore_cache()
 
 
+@pytest.mark.parametrize("layout", [2, 3])
+def test_dispatch_without_a_tuned_shape_uses_the_built_in_default(layout):
+    """No shape is tuned for these storage layouts, so sgemm_tuned() runs the built-in default
+    configuration (with split K on the long-K shape)."""
+    for shape in [(300, 200, 150), (96, 1000, 4100), (1536, 1536, 64)]:
+        M, N, K = shape
+        A, B, C = synth.make_inputs(M, N, K, layout, seed=74 + layout)
+        assert b.sgemm_config_get(M, N, K, layout) is None
+        cfg = b.sgemm_config_select(M, N, K, layout)
+        assert cfg.as_tuple() == b.sgemm_config_default(M, N, K, layout).as_tuple()
+        got = gu.run_gpu(None, A, B, C, 1.0, 0.5, layout, entry="tuned")
+        gu.check_against_oracle(got, A, B, C, 1.0, 0.5, layout, what=f"{shape} layout {layout} {cfg}")
+
+
 def test_launch_on_a_side_stream_and_on_the_set_stream():
     import torch
     cfg = _some_configs()[1]

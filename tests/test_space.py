@@ -91,3 +91,29 @@ def test_invalid_examples():
     big = b.make_config(256, 256, 64, 16, 16, 4, 4, 1, 1, 0, 8, 1, 0)
     assert b.sgemm_config_lds_bytes(big) == 2 * 4 * (2 * 256 * 64) > 160 * 1024
     assert b.sgemm_config_check(big) == b.E_INVALID
+
+
+def test_predicted_lds_size_matches_the_compiled_variants(tmp_path):
+    """The LDS model that prunes the space (oracle and library) against what the compiler
+    really allocates, for a few variants of every preset, in the layout that needs most."""
+    import os
+    b.sgemm_kernel_cache_dir(str(tmp_path))
+    try:
+        for preset in (b.SPACE_FULL, b.SPACE_MFMA, b.SPACE_EXT, b.SPACE_DIRECT):
+            n = b.sgemm_space_size(preset)
+            rng = np.random.default_rng(100 + preset)
+            checked = 0
+            for i in rng.choice(n, size=40, replace=False):
+                c = b.sgemm_space_get(preset, int(i))
+                if c.mdimc * c.ndimc > 256 or c.mwg * c.nwg > 128 * 128:
+                    continue            # keep to variants that compile in about a second
+                t = c.as_tuple()
+                layout = max(range(4), key=lambda l: so.lds_bytes(t, l))
+                info = b.sgemm_kernel_compile(c, layout, 0)
+                assert info.lds_bytes == so.lds_bytes(t, layout) == b.sgemm_config_lds_bytes(c), t
+                checked += 1
+                if checked == 4:
+                    break
+            assert checked >= 2
+    finally:
+        b.sgemm_kernel_cache_dir(os.path.join(os.path.dirname(b.LIB_PATH), "kcache"))
