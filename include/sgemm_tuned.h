@@ -129,7 +129,8 @@ typedef struct tune_opts {
     float pso_alpha;    /* probability of a random value per dimension; default 0.4       */
     float pso_beta;     /* probability of the particle's own best; default 0              */
     float pso_gamma;    /* probability of the swarm's best; default 0.4                   */
-    float random_fraction; /* random search: fraction of the space if budget <= 0         */
+    float random_fraction; /* random search: fraction of the space if budget <= 0, rounded
+                              down to whole configurations (at least 1)                       */
     const float *A;     /* optional caller-owned DEVICE operands in the call's layout;    */
     const float *B;     /*   when A is null the library allocates seeded synthetic ones   */
     float *C;           /*   (C is overwritten; C_in is restored from C0 before each run) */

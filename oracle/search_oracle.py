@@ -15,7 +15,9 @@ and the two traces can be compared element by element.
 Readings where the paper is silent (the library documents the same ones):
   - budget = number of DISTINCT configurations whose cost is asked for; a revisit is free;
     a search also stops after 20*budget moves.
-  - random search: the first `budget` steps of a Fisher-Yates shuffle of 0..n-1.
+  - random search: the first `budget` steps of a Fisher-Yates shuffle of 0..n-1.  A budget
+    given as a fraction of the space is rounded down (the paper explores 1/2048 of 241 600
+    configurations as 117 and 1/32 of 3424 as 107), but is at least 1.
   - annealing: start s = below(n), or a given configuration (then no draw is made: a search
     may be continued from a known good point).  Neighbours of s = valid configurations differing from s
     in exactly one parameter, ordered by parameter then by position in its value list; s' is
@@ -108,7 +110,7 @@ def full_search(configs, t):
 def random_search(configs, t, budget, seed, fraction=0.0):
     n = len(configs)
     if budget <= 0:
-        budget = math.ceil(fraction * n)
+        budget = max(1, math.floor(fraction * n))
     budget = max(1, min(budget, n))
     costs = _Costs(t, budget)
     rng = SplitMix64(seed)

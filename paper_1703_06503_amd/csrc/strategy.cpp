@@ -162,7 +162,7 @@ SearchResult run_search(const Space &space, int strategy, int budget, uint64_t s
     int b = budget;
     if (strategy == SGEMM_STRATEGY_FULL) b = n;
     if (strategy == SGEMM_STRATEGY_RANDOM && b <= 0)
-        b = (int)std::ceil(params.random_fraction * n);
+        b = (int)std::floor(params.random_fraction * n); // the paper's 1/2048 of 241 600 is 117
     if (b < 1) b = 1;
     if (b > n) b = n;
     Evaluator ev(cost, n, b);

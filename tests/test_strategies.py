@@ -71,13 +71,33 @@ def test_random_search_samples_without_replacement_and_fraction_one_is_full():
     r = so.random_search(small, ts, 0, seed=5, fraction=1.0)
     assert sorted(r["visited"]) == list(range(16))
     assert r["best_index"] == so.full_search(small, ts)["best_index"]
-    # a fraction is rounded up to whole configurations
+    # a fraction is rounded down to whole configurations, but at least one is explored
     assert so.random_search(small, ts, 0, seed=5, fraction=1 / 32)["evaluations"] == 1
+    assert so.random_search(small, ts, 0, seed=5, fraction=3.9 / 16)["evaluations"] == 3
     # uniformity: every configuration is equally likely to be the first pick
     first = np.bincount([so.random_search(small, ts, 1, seed=s)["visited"][0] for s in range(3200)],
                         minlength=16)
     chi2 = float(((first - 200.0) ** 2 / 200.0).sum())
     assert chi2 < 45.0          # 15 degrees of freedom, far tail
+
+
+def test_budget_from_a_fraction_matches_the_numbers_the_paper_prints():
+    """tests/golden/paper_search_budgets.txt: 1/32 of 3424 -> 107, 1/2048 of 241 600 -> 117."""
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "paper_search_budgets.txt")
+    rows = [tuple(int(x) for x in line.split()) for line in open(path)
+            if line.strip() and not line.startswith("#")]
+    assert rows == [(3424, 32, 107), (241600, 2048, 117)]
+    for n, denom, explored in rows:
+        configs = [(i,) for i in range(n)]
+        t = np.ones(n, dtype=np.float32)
+        r = so.random_search(configs, t, 0, seed=1, fraction=1.0 / denom)
+        assert r["evaluations"] == explored and len(set(r["visited"])) == explored
+    # the library rounds the same way on its own spaces
+    n = b.sgemm_space_size(b.SPACE_FULL)
+    t = np.ones(n, dtype=np.float32)
+    ev, _, visited = b.tune_replay(b.SPACE_FULL, t, b.STRATEGY_RANDOM, 0, 1, _opts(random_fraction=1 / 2048))
+    assert ev == n // 2048 == len(visited)
 
 
 def test_annealing_limits():
