@@ -6,10 +6,11 @@
 One step = one sgemm_tuned() call on the resident synthetic operands of the workload: the
 per-shape cache lookup, variant dispatch and the generated kernel (workgroup tiling, LDS
 staging, MFMA inner product, epilogue).  Before the timed region the tuner itself runs on the
-same operands (particle swarm over the matrix-core space, every evaluated variant verified
-against the device reference kernel), so the configuration that is timed is the one the
-library found; the committed table of earlier tuning results is loaded first and only
-replaced by a faster finding.  Prints one JSON line.
+same operands (a cold particle-swarm search over the matrix-core space, every evaluated variant
+verified against the device reference kernel); the committed table of earlier tuning results
+is loaded first and only replaced by a faster finding, so the configuration that is timed is
+the best the library knows.  The JSON line also says after how many evaluations the cold
+search had measured a configuration within 5 % of it.  Prints one JSON line.
 """
 import argparse
 import json
@@ -93,7 +94,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--tune-budget", type=int, default=32,
+    ap.add_argument("--tune-budget", type=int, default=64,
                     help="configurations the in-run search may evaluate (0 = no search)")
     ap.add_argument("--workload", default="cfg4_4096")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -121,11 +122,16 @@ def main():
     tuning = {"budget": a.tune_budget}
     cached = b.sgemm_config_get(w.M, w.N, w.K, w.layout)
     tuning["cached_config"] = cached.as_dict() if cached is not None else None
+    search_log = None
     if a.tune_budget > 0:
+        import tempfile
+        # a cold search (random start, as in the paper): how many evaluations it takes to get
+        # within 5 % of the best known configuration is the second half of the metric
+        search_log = os.path.join(tempfile.mkdtemp(prefix="sgemm_bench_"), "search.jsonl")
         opts = b.tune_opts()
         opts.space = b.SPACE_MFMA
         opts.pso_S = 6
-        opts.warm_start = 1        # particle 0 starts at the cached configuration
+        opts.log_path = search_log.encode()
         opts.A, opts.B, opts.C, opts.C0 = dA.data_ptr(), dB.data_ptr(), dC.data_ptr(), dC0.data_ptr()
         opts.lda, opts.ldb, opts.ldc = lda, ldb, ldc
         t0 = time.perf_counter()
@@ -172,6 +178,19 @@ def main():
     if not ratio <= 1.0:
         print(f"bench.py: result outside the parity bound (err/bound = {ratio})", file=sys.stderr)
         return 1
+
+    if search_log is not None and os.path.exists(search_log):
+        # evaluations of the cold search until a configuration within 5 % of the time of the
+        # configuration that was finally timed had been measured (null: never, in this budget)
+        target = 1.05 * kernel_ms
+        hit = None
+        with open(search_log) as f:
+            for i, line in enumerate(f):
+                r = json.loads(line)
+                if r["status"].startswith("ok") and 0 < r["ms"] <= target:
+                    hit = i + 1
+                    break
+        tuning["evals_to_within_5pct_of_best"] = hit
 
     value = flops / (ms_per_step * 1e-3) * 1e-9
     achieved_tflops = flops / (kernel_ms * 1e-3) * 1e-12
