@@ -235,6 +235,9 @@ int sgemm_kernel_cache_dir(const char *path);
  * bounds-guarded form.  cfg->sk > 1 selects the build that split-K launches use (one build
  * for every sk > 1: the split itself is a launch parameter).  Needs no GPU.  info may be null. */
 int sgemm_kernel_compile(const sgemm_config *cfg, int layout, int edge, sgemm_kernel_info *info);
+/* [host] Path of the variant's code object in the cache directory (whether or not it exists
+ * yet), NUL-terminated into buf: lets a deployment ship exactly the variants it uses. */
+int sgemm_kernel_cache_path(const sgemm_config *cfg, int layout, int edge, char *buf, int cap);
 /* [host] The -D macro string the variant is compiled with, NUL-terminated into buf. */
 int sgemm_kernel_macros(const sgemm_config *cfg, int layout, int edge, char *buf, int cap);
 

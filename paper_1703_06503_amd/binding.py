@@ -89,7 +89,8 @@ EXPORTS = (
     "sgemm_space_get", "sgemm_space_find", "sgemm_space_dims", "sgemm_space_values",
     "sgemm_config_check", "sgemm_config_lds_bytes", "sgemm_config_default",
     "sgemm_config_workspace_bytes",
-    "sgemm_kernel_cache_dir", "sgemm_kernel_compile", "sgemm_kernel_macros", "sgemm_config_get",
+    "sgemm_kernel_cache_dir", "sgemm_kernel_compile", "sgemm_kernel_macros",
+    "sgemm_kernel_cache_path", "sgemm_config_get",
     "sgemm_config_set", "sgemm_config_select", "sgemm_cache_load", "sgemm_cache_save",
     "sgemm_cache_clear", "sgemm_cache_count", "sgemm_device_peak", "sgemm_status_string",
     "sgemm_last_error",
@@ -310,6 +311,13 @@ def sgemm_kernel_compile(cfg, layout=0, edge=0):
     _check(lib().sgemm_kernel_compile(ctypes.byref(cfg), layout, edge, ctypes.byref(info)),
            "sgemm_kernel_compile")
     return info
+
+
+def sgemm_kernel_cache_path(cfg, layout=0, edge=0):
+    buf = ctypes.create_string_buffer(4096)
+    _check(lib().sgemm_kernel_cache_path(ctypes.byref(cfg), layout, edge, buf, 4096),
+           "sgemm_kernel_cache_path")
+    return os.fsdecode(buf.value)
 
 
 def sgemm_kernel_macros(cfg, layout=0, edge=0):

@@ -150,7 +150,9 @@ void read_code_object_info(const std::vector<char> &image, sgemm_kernel_info *in
     if (find_uint(image, ".private_segment_fixed_size", &v)) info->scratch_bytes = (int)v;
 }
 
-int get_code_object(const VariantKey &key, CodeObject *out, std::string *log) {
+// File of a variant's code object in the cache directory: a hash of the kernel source, the
+// macros, the compiler flags, any experiment defines and the compiler's identity.
+std::string code_object_path(const VariantKey &key) {
     const std::string macros = key.macros();
     const size_t src_len = (size_t)(sgemm_kernel_source_end - sgemm_kernel_source_begin);
     uint64_t h = fnv1a(sgemm_kernel_source_begin, src_len);
@@ -163,8 +165,15 @@ int get_code_object(const VariantKey &key, CodeObject *out, std::string *log) {
     h = compiler_identity(h);
     char name[40];
     std::snprintf(name, sizeof name, "/%016llx.hsaco", (unsigned long long)h);
+    return cache_dir() + name;
+}
+
+int get_code_object(const VariantKey &key, CodeObject *out, std::string *log) {
+    const std::string macros = key.macros();
+    const char *extra_env = std::getenv("SGEMM_TUNED_EXTRA_DEFINES");
+    const std::string extra = extra_env ? extra_env : "";
+    const std::string path = code_object_path(key);
     const std::string dir = cache_dir();
-    const std::string path = dir + name;
 
     out->info = sgemm_kernel_info{};
     if (read_file(path, &out->image)) {

@@ -32,6 +32,9 @@ struct CodeObject {
 // and, if log is non-null, the compiler's message.
 int get_code_object(const VariantKey &key, CodeObject *out, std::string *log);
 
+// Where the variant's code object is (or will be) kept in the cache directory.
+std::string code_object_path(const VariantKey &key);
+
 void set_cache_dir(const std::string &path);
 std::string cache_dir();
 

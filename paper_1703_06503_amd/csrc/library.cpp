@@ -560,6 +560,15 @@ int sgemm_kernel_compile(const sgemm_config *cfg, int layout, int edge, sgemm_ke
     return rc;
 }
 
+int sgemm_kernel_cache_path(const sgemm_config *cfg, int layout, int edge, char *buf, int cap) {
+    if (!cfg || !buf || cap <= 0 || layout < 0 || layout > 3) return SGEMM_E_BADARG;
+    if (violates(*cfg)) return SGEMM_E_INVALID;
+    const std::string p = code_object_path(VariantKey{*cfg, layout, edge ? 1 : 0, cfg->sk > 1 ? 1 : 0});
+    if ((int)p.size() + 1 > cap) return SGEMM_E_BADARG;
+    std::memcpy(buf, p.c_str(), p.size() + 1);
+    return SGEMM_OK;
+}
+
 int sgemm_kernel_macros(const sgemm_config *cfg, int layout, int edge, char *buf, int cap) {
     if (!cfg || !buf || cap <= 0) return SGEMM_E_BADARG;
     const std::string m = VariantKey{*cfg, layout, edge ? 1 : 0, cfg->sk > 1 ? 1 : 0}.macros();

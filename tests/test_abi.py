@@ -72,6 +72,10 @@ def test_kernel_generator_compiles_without_a_gpu(tmp_path):
         assert b.sgemm_config_lds_bytes(cfg) == 2 * 4 * (64 * 20 + 64 * 20)   # worst layout
         assert b.sgemm_kernel_compile(cfg, 2, 0).lds_bytes == 2 * 4 * (64 * 20 + 64 * 20)
         assert info.agprs + info.vgprs >= 64            # 8 x 8 accumulators per lane
+        where = b.sgemm_kernel_cache_path(cfg, 0, 1)
+        assert where.startswith(str(tmp_path)) and where.endswith(".hsaco") and os.path.exists(where)
+        assert b.sgemm_kernel_cache_path(cfg, 0, 0) != where
+        assert not os.path.exists(b.sgemm_kernel_cache_path(cfg, 0, 0))
         again = b.sgemm_kernel_compile(cfg, 0, 1)
         assert again.from_cache == 1 and again.code_bytes == info.code_bytes
         macros = b.sgemm_kernel_macros(cfg, 3, 1)
