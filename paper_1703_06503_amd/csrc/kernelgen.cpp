@@ -150,12 +150,46 @@ void read_code_object_info(const std::vector<char> &image, sgemm_kernel_info *in
     if (find_uint(image, ".private_segment_fixed_size", &v)) info->scratch_bytes = (int)v;
 }
 
-// File of a variant's code object in the cache directory: a hash of the kernel source, the
-// macros, the compiler flags, any experiment defines and the compiler's identity.
+// The kernel source with comments removed, runs of blanks collapsed and blank lines dropped:
+// what the cache key is computed from, so that rewording a comment does not invalidate every
+// cached variant.  Line breaks are kept (they end preprocessor directives).
+const std::string &normalized_source() {
+    static const std::string text = [] {
+        const char *p = sgemm_kernel_source_begin, *end = sgemm_kernel_source_end;
+        std::string out;
+        out.reserve((size_t)(end - p));
+        int gap = 0; // 0 = none, 1 = blanks, 2 = at least one line break
+        while (p < end) {
+            if (p + 1 < end && p[0] == '/' && p[1] == '/') {
+                while (p < end && *p != '\n') ++p;
+            } else if (p + 1 < end && p[0] == '/' && p[1] == '*') {
+                p += 2;
+                while (p + 1 < end && !(p[0] == '*' && p[1] == '/')) ++p;
+                p = (p + 1 < end) ? p + 2 : end;
+                if (gap < 1) gap = 1;
+            } else if (*p == '\n') {
+                gap = 2;
+                ++p;
+            } else if (*p == ' ' || *p == '\t' || *p == '\r') {
+                if (gap < 1) gap = 1;
+                ++p;
+            } else {
+                if (gap && !out.empty()) out.push_back(gap == 2 ? '\n' : ' ');
+                gap = 0;
+                out.push_back(*p++);
+            }
+        }
+        return out;
+    }();
+    return text;
+}
+
+// File of a variant's code object in the cache directory: a hash of the kernel source (without
+// comments), the macros, the compiler flags, any experiment defines and the compiler's identity.
 std::string code_object_path(const VariantKey &key) {
     const std::string macros = key.macros();
-    const size_t src_len = (size_t)(sgemm_kernel_source_end - sgemm_kernel_source_begin);
-    uint64_t h = fnv1a(sgemm_kernel_source_begin, src_len);
+    const std::string &src = normalized_source();
+    uint64_t h = fnv1a(src.data(), src.size());
     h = fnv1a(macros.data(), macros.size(), h);
     for (const char *f : kCompilerFlags) h = fnv1a(f, std::strlen(f), h);
     // extra -D options for kernel experiments (space separated); part of the cache key
