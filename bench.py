@@ -26,27 +26,26 @@ PEAK_FP32_TFLOPS = 157.3   # MI355X published dense FP32 (vector and matrix)
 
 # HBM-side bytes per launch (L2 fetches + writes) from `rocprofv3 --pmc FETCH_SIZE` and
 # `--pmc WRITE_SIZE` runs of this script, each scaled by what the same counter reads for a
-# 64 MiB device-to-device copy (FETCH_SIZE x1.9989, WRITE_SIZE x1.000).  Keyed by workload
-# and by the variant that was timed; the summaries are under profiles/.  A variant that has
-# not been measured reports null.
+# 64 MiB device-to-device copy (FETCH_SIZE x1.9989, WRITE_SIZE x1.000).  What leaves the L2s
+# is set by the tile, the order in which tiles are dealt to the eight XCDs, and the split of K,
+# so measurements are keyed by workload and (MWG, NWG, GRP, SK); the summaries are under
+# profiles/.  A variant with another tile or order reports null.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/sgemm_tuned_cfg4_4096.txt: 576.59 MiB fetched + 64.00 MiB written
-    ("cfg4_4096", (256, 256, 32, 32, 8, 4, 4, 1, 1, 0, 8, 1, 0, 1, 2)): (576.59 + 64.00) * 2 ** 20,
-    # an earlier winner (16 x 16 threads, padded LDS rows), same tile and tile order
-    ("cfg4_4096", (256, 256, 32, 16, 16, 4, 4, 1, 1, 1, 8, 1, 0, 1, 2)): (295454 * 1.9989 + 65536) * 1024,
+    # profiles/sgemm_tuned_cfg4_4096.txt: 576.59 MiB fetched + 64.00 MiB written (row-major
+    # tile order: every XCD reads all of A and 2/16 of B)
+    ("cfg4_4096", (256, 256, 0, 1)): (576.59 + 64.00) * 2 ** 20,
+    # XCD-aware order, each XCD a 4 x 8 block of tiles: 384 MiB fetched + 64 MiB written
+    ("cfg4_4096", (256, 256, 1, 1)): (196657 * 1.9989 + 65536) * 1024,
     # profiles/sgemm_tuned_cfg1_256.txt, sgemm_tuned_cfg5_*.txt (GEMM launch + plane reduction)
-    ("cfg1_256", (64, 32, 32, 32, 8, 4, 1, 1, 1, 0, 8, 2, 1, 1, 2)): (2.30 + 0.25) * 2 ** 20,
-    ("cfg5_128x4096x4096", (64, 128, 32, 16, 16, 4, 4, 1, 1, 0, 2, 1, 1, 8, 2)):
-        (80.07 + 16.00 + 16.03 + 2.00) * 2 ** 20,
-    ("cfg5_4096x64x9216", (128, 64, 64, 32, 16, 4, 4, 1, 1, 0, 2, 1, 0, 8, 2)):
-        (161.99 + 8.00 + 8.03 + 1.00) * 2 ** 20,
+    ("cfg1_256", (64, 32, 1, 1)): (2.30 + 0.25) * 2 ** 20,
+    ("cfg5_128x4096x4096", (64, 128, 1, 8)): (80.07 + 16.00 + 16.03 + 2.00) * 2 ** 20,
+    ("cfg5_4096x64x9216", (128, 64, 0, 8)): (161.99 + 8.00 + 8.03 + 1.00) * 2 ** 20,
 }
 
 
 def config_key(cfg):
     d = cfg.as_dict()
-    return tuple(d[k] for k in ("mwg", "nwg", "kwg", "mdimc", "ndimc", "vwm", "vwn", "sa", "sb",
-                                "pad", "kwi", "mfma", "grp", "sk", "ns"))
+    return tuple(d[k] for k in ("mwg", "nwg", "grp", "sk"))
 
 
 def cpu_baseline(w, A, B, C, target_seconds=12.0):
@@ -191,6 +190,8 @@ def main():
                     hit = i + 1
                     break
         tuning["evals_to_within_5pct_of_best"] = hit
+        import shutil
+        shutil.rmtree(os.path.dirname(search_log), ignore_errors=True)
 
     value = flops / (ms_per_step * 1e-3) * 1e-9
     achieved_tflops = flops / (kernel_ms * 1e-3) * 1e-12

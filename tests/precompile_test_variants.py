@@ -15,8 +15,20 @@ from tests import gpu_util as gu                         # noqa: E402
 from tests import test_gpu_parity as t                   # noqa: E402
 
 
+def tuned_table_variants():
+    """The variants that sgemm_tuned() launches for the shapes of the committed table of tuned
+    configurations (what bench.py, smoke() and the full-size tests run)."""
+    from paper_1703_06503_amd import report
+    table = os.path.join(os.path.dirname(b.LIB_PATH), "..", "tuned_configs.txt")
+    for M, N, K, layout, _ms, cfg in report.read_table(table):
+        c = b.make_config(*cfg)
+        edge = 1 if (M % c.mwg or N % c.nwg or K % c.kwg) else 0
+        b.sgemm_kernel_compile(c, layout, edge)
+
+
 def main():
     jobs = min(8, os.cpu_count() or 1)
+    tuned_table_variants()
     precompile(b.SPACE_SMALL, (0,), (0,), jobs)
     full = gu.sample_configs(**t.FULL_SAMPLE)
     precompile(b.SPACE_FULL, (0,), (0, 1), jobs, indices=full)
