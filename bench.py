@@ -97,6 +97,10 @@ def main():
                     help="configurations the in-run search may evaluate (0 = no search)")
     ap.add_argument("--workload", default="cfg4_4096")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--rotate", type=int, default=1,
+                    help="cycle the timed calls through this many copies of the operands, so that "
+                         "each call finds A and B in HBM rather than in the 256 MiB last-level "
+                         "cache (for HBM-bound shapes; default 1 = the same operands every call)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (--gpus 1); sharding across several "
@@ -143,8 +147,13 @@ def main():
         })
     used = b.sgemm_config_select(w.M, w.N, w.K, w.layout)
 
+    sets = [(dA, dB, dC)] + [(dA.clone(), dB.clone(), dC.clone()) for _ in range(max(a.rotate, 1) - 1)]
+    calls = [0]
+
     def step():
-        b.sgemm_tuned_on(None, w.M, w.N, w.K, w.alpha, dA, lda, dB, ldb, w.beta, dC, ldc, w.layout)
+        xA, xB, xC = sets[calls[0] % len(sets)]
+        calls[0] += 1
+        b.sgemm_tuned_on(None, w.M, w.N, w.K, w.alpha, xA, lda, xB, ldb, w.beta, xC, ldc, w.layout)
 
     dC.copy_(dC0)
     for _ in range(a.warmup):
@@ -167,8 +176,9 @@ def main():
     from oracle import sgemm_oracle as orc
     if w.beta != 0.0:
         dC.copy_(dC0)
-        step()
-        torch.cuda.synchronize()
+    calls[0] = 0                       # the checked result is the first operand set's
+    step()
+    torch.cuda.synchronize()
     got = dC.cpu().numpy()
     r, c = synth.sample_positions(w.M, w.N, w.seed, rows=4, cols=4, scattered=1024)
     ref = orc.sgemm_sample(w.alpha, A, B, w.beta, C, r, c, w.layout)
@@ -211,7 +221,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{a.workload}: SGEMM M={w.M} N={w.N} K={w.K} alpha={w.alpha} "
                                f"beta={w.beta} layout={w.layout}, {w.dist} seed {w.seed}",
-                   "kernel_config": used.as_dict()},
+                   "kernel_config": used.as_dict(), "operand_sets": len(sets)},
         "pct_of_fp32_peak": 100.0 * value / (PEAK_FP32_TFLOPS * 1e3),
         "device": {"compute_units": cus, "clock_mhz": mhz, "fp32_peak_gflops_from_device": peak_gflops},
         "parity_err_over_bound": ratio,
