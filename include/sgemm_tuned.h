@@ -173,6 +173,20 @@ int sgemm_tuned_on(void *hip_stream, int M, int N, int K, float alpha, const flo
                    const float *B, int ldb, float beta, float *C, int ldc, int layout);
 int sgemm_set_stream(void *hip_stream);
 
+/* The same call with on-line tuning (the paper's other mode of use: tuning "at run time, in the
+ * first calls", section "CLTune: an auto-tuner for OpenCL kernels").  While (M,N,K,layout) has
+ * no entry in the per-shape cache, every call computes its GEMM with the next configuration
+ * that `strategy` proposes in `space` and times that one launch (the call then returns only when
+ * the launch has finished); after `budget` distinct configurations the fastest one is put into
+ * the cache and all later calls are ordinary asynchronous sgemm_tuned_on() calls.  Every call
+ * returns a correct C.  A configuration that fails to compile, spills or fails to launch counts
+ * as evaluated and the same call goes on to the next one.  Candidates are timed once, cold, and
+ * are not re-verified against the reference kernel: a quick, noisy search compared with tune().
+ * Calls for one shape must not overlap in time while it is being tuned. */
+int sgemm_tuned_online(void *hip_stream, int M, int N, int K, float alpha, const float *A, int lda,
+                       const float *B, int ldb, float beta, float *C, int ldc, int layout,
+                       int space, int strategy, int budget);
+
 /* Same operation with an explicit configuration (what the tuner times and the parity tests
  * drive).  Returns SGEMM_E_INVALID if `cfg` breaks a constraint; picks the guarded-edge
  * build of the variant when M, N, K are not multiples of the tile, and narrows vwm/vwn to 1

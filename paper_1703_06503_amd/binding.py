@@ -84,7 +84,8 @@ class tune_result(ctypes.Structure):
 
 
 EXPORTS = (
-    "sgemm_tuned", "sgemm_tuned_on", "sgemm_set_stream", "sgemm_run_config", "sgemm_reference",
+    "sgemm_tuned", "sgemm_tuned_on", "sgemm_tuned_online", "sgemm_set_stream", "sgemm_run_config",
+    "sgemm_reference",
     "tune", "tune_ex", "tune_replay", "sgemm_space_size", "sgemm_space_raw_size",
     "sgemm_space_get", "sgemm_space_find", "sgemm_space_dims", "sgemm_space_values",
     "sgemm_config_check", "sgemm_config_lds_bytes", "sgemm_config_default",
@@ -121,6 +122,7 @@ def lib():
         gemm = [i, i, i, f, vp, i, vp, i, f, vp, i, i]
         L.sgemm_tuned.argtypes = gemm
         L.sgemm_tuned_on.argtypes = [vp] + gemm
+        L.sgemm_tuned_online.argtypes = [vp] + gemm + [i, i, i]
         L.sgemm_set_stream.argtypes = [vp]
         L.sgemm_run_config.argtypes = [vp, cfgp] + gemm
         L.sgemm_reference.argtypes = [vp] + gemm
@@ -207,6 +209,13 @@ def sgemm_tuned(M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, layout=0):
 def sgemm_tuned_on(stream, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, layout=0):
     return _check(lib().sgemm_tuned_on(_stream(stream), M, N, K, alpha, _ptr(A), lda, _ptr(B),
                                        ldb, beta, _ptr(C), ldc, layout), "sgemm_tuned_on")
+
+
+def sgemm_tuned_online(stream, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, layout=0,
+                       space=SPACE_MFMA, strategy=STRATEGY_ANNEALING, budget=32):
+    return _check(lib().sgemm_tuned_online(_stream(stream), M, N, K, alpha, _ptr(A), lda, _ptr(B),
+                                           ldb, beta, _ptr(C), ldc, layout, space, strategy, budget),
+                  "sgemm_tuned_online")
 
 
 def sgemm_set_stream(stream):

@@ -7,6 +7,7 @@
 #include <algorithm>
 #include <chrono>
 #include <cmath>
+#include <condition_variable>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -14,6 +15,7 @@
 #include <memory>
 #include <mutex>
 #include <string>
+#include <thread>
 #include <tuple>
 #include <vector>
 
@@ -404,6 +406,37 @@ struct Event {
     ~Event() { if (e) (void)hipEventDestroy(e); }
 };
 
+// ---- on-line tuning ------------------------------------------------------------------------
+// The paper also proposes tuning at run time, in the first calls of an application ("CLTune:
+// an auto-tuner for OpenCL kernels").  One search per problem shape runs in a thread of its
+// own; its cost function hands the next configuration to the GEMM call that is waiting for
+// one and blocks until that call reports the time it measured, so the four strategies are
+// used exactly as they are.
+struct OnlineSearch {
+    std::mutex mu;
+    std::condition_variable cv;
+    std::thread worker;
+    int wanted = -1;        // configuration the search wants timed next (-1: none yet)
+    double reported = 0.0;  // its time, once has_report is set
+    bool has_report = false;
+    bool finished = false;  // the search has ended; best_index holds its result
+    bool abandoned = false; // the library is shutting the search down
+    int best_index = -1;
+    double best_ms = 0.0;
+    int evaluations = 0;
+
+    ~OnlineSearch() {
+        {
+            std::lock_guard<std::mutex> lock(mu);
+            abandoned = true;
+        }
+        cv.notify_all();
+        if (worker.joinable()) worker.join();
+    }
+};
+std::mutex g_online_mu;
+std::map<std::tuple<int, int, int, int, int>, std::unique_ptr<OnlineSearch>> g_online; // + space
+
 double median(std::vector<double> v) {
     std::sort(v.begin(), v.end());
     const size_t n = v.size();
@@ -457,6 +490,110 @@ int sgemm_tuned_on(void *hip_stream, int M, int N, int K, float alpha, const flo
     }
     return run_config(static_cast<hipStream_t>(hip_stream), cfg, M, N, K, alpha, A, lda, B, ldb, beta,
                       C, ldc, layout);
+}
+
+int sgemm_tuned_online(void *hip_stream, int M, int N, int K, float alpha, const float *A, int lda,
+                       const float *B, int ldb, float beta, float *C, int ldc, int layout,
+                       int space_id, int strategy, int budget) {
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const int rc0 = check_gemm_args(M, N, K, A, lda, B, ldb, C, ldc, layout, alpha != 0.0f);
+    if (rc0 != SGEMM_OK) return rc0;
+    const Space *space = get_space(space_id);
+    if (!space || strategy < 0 || strategy > 3) return SGEMM_E_BADARG;
+    if (space->configs.empty()) return SGEMM_E_NOCONFIG;
+    // nothing to time, or already tuned: the ordinary asynchronous call
+    bool tuned;
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        autoload_locked();
+        tuned = g_tuned.count(ShapeKey{M, N, K, layout}) != 0;
+    }
+    if (tuned || M == 0 || N == 0 || K == 0 || alpha == 0.0f || budget <= 0)
+        return sgemm_tuned_on(hip_stream, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, layout);
+
+    OnlineSearch *os;
+    {
+        std::lock_guard<std::mutex> lock(g_online_mu);
+        auto &slot = g_online[std::make_tuple(M, N, K, layout, space_id)];
+        if (!slot) {
+            slot.reset(new OnlineSearch);
+            OnlineSearch *self = slot.get();
+            const uint64_t seed = ((uint64_t)M * 1000003ull + (uint64_t)N) * 1000003ull + (uint64_t)K + (uint64_t)layout;
+            self->worker = std::thread([self, space, strategy, budget, seed] {
+                const SearchResult r = run_search(*space, strategy, budget, seed, StrategyParams{}, [self](int idx) {
+                    std::unique_lock<std::mutex> lock(self->mu);
+                    self->wanted = idx;
+                    self->has_report = false;
+                    self->cv.notify_all();
+                    self->cv.wait(lock, [self] { return self->has_report || self->abandoned; });
+                    self->wanted = -1;
+                    return self->abandoned ? -1.0 : self->reported;
+                });
+                std::lock_guard<std::mutex> lock(self->mu);
+                self->best_index = r.best_index;
+                self->best_ms = r.best_cost;
+                self->evaluations = r.evaluations;
+                self->finished = true;
+                self->cv.notify_all();
+            });
+        }
+        os = slot.get();
+    }
+
+    // One GEMM per call, done by the next candidate that compiles and launches; a candidate
+    // that does not is reported as failed and the search is asked for another one.
+    Event ev0, ev1;
+    for (;;) {
+        int idx;
+        {
+            std::unique_lock<std::mutex> lock(os->mu);
+            os->cv.wait(lock, [os] { return os->finished || (os->wanted >= 0 && !os->has_report); });
+            if (os->finished) break;
+            idx = os->wanted;
+        }
+        const sgemm_config cfg = from_point(space->configs[idx]);
+        double ms = -1.0;
+        int launched = SGEMM_E_LAUNCH;
+        do {
+            const VariantKey key = resolve_variant(cfg, M, N, K, A, lda, B, ldb, C, ldc, layout);
+            std::shared_ptr<LoadedKernel> k;
+            if (get_loaded(key, &k) != SGEMM_OK) break;
+            if (k->info.scratch_bytes > 0 || k->info.lds_bytes > kLdsLimitBytes) break;
+            (void)hipEventRecord(ev0.e, s);
+            launched = launch_loaded(s, *k, key.cfg, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc);
+            if (launched != SGEMM_OK) break;
+            (void)hipEventRecord(ev1.e, s);
+            if (hipEventSynchronize(ev1.e) != hipSuccess) { launched = SGEMM_E_LAUNCH; break; }
+            float e = 0.0f;
+            (void)hipEventElapsedTime(&e, ev0.e, ev1.e);
+            ms = e;
+        } while (false);
+        {
+            std::lock_guard<std::mutex> lock(os->mu);
+            os->reported = ms;
+            os->has_report = true;
+        }
+        os->cv.notify_all();
+        if (launched == SGEMM_OK) return SGEMM_OK; // this call's GEMM is done
+    }
+    // the search is over: keep its winner, drop the search, and serve this call normally
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        if (os->best_index >= 0) {
+            g_tuned[ShapeKey{M, N, K, layout}] = Tuned{from_point(space->configs[os->best_index]), (float)os->best_ms};
+        } else {
+            // nothing in the space worked here: settle on what the dispatch would pick anyway,
+            // so that the next call does not start the search over
+            sgemm_config fallback;
+            select_config_locked(M, N, K, layout, &fallback);
+            g_tuned[ShapeKey{M, N, K, layout}] = Tuned{fallback, 0.0f};
+        }
+    }
+    {
+        std::lock_guard<std::mutex> lock(g_online_mu);
+        g_online.erase(std::make_tuple(M, N, K, layout, space_id));
+    }
+    return sgemm_tuned_on(hip_stream, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, layout);
 }
 
 int sgemm_tuned(int M, int N, int K, float alpha, const float *A, int lda, const float *B, int ldb,

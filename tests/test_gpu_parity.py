@@ -422,6 +422,37 @@ def test_dispatch_without_a_tuned_shape_uses_the_built_in_default(layout):
         gu.check_against_oracle(got, A, B, C, 1.0, 0.5, layout, what=f"{shape} layout {layout} {cfg}")
 
 
+@pytest.mark.parametrize("strategy", [b.STRATEGY_ANNEALING, b.STRATEGY_PSO, b.STRATEGY_FULL])
+def test_online_tuning_settles_on_a_configuration_and_every_call_is_correct(strategy):
+    """Tuning in the first calls: each call computes its GEMM with the configuration the search
+    wants timed next; after the budget the winner is in the per-shape cache."""
+    import torch
+    M, N, K = 320, 256, 192
+    A, B, C = synth.make_inputs(M, N, K, 0, seed=75)
+    dA, dB, dC0 = (torch.from_numpy(x).cuda() for x in (A, B, C))
+    dC = dC0.clone()
+    ref = orc.sgemm(1.25, A, B, 0.5, C, 0)
+    budget = 6 if strategy != b.STRATEGY_FULL else 0      # full search ignores the budget
+    b.sgemm_cache_clear()
+    try:
+        settled_after = None
+        for call in range(24):
+            dC.copy_(dC0)
+            b.sgemm_tuned_online(None, M, N, K, 1.25, dA, K, dB, N, 0.5, dC, N, 0,
+                                 space=b.SPACE_SMALL, strategy=strategy, budget=max(budget, 1))
+            torch.cuda.synchronize()
+            gu.check_against_oracle(dC.cpu().numpy(), A, B, C, 1.25, 0.5, 0, ref, what=f"call {call}")
+            if settled_after is None and b.sgemm_config_get(M, N, K, 0) is not None:
+                settled_after = call
+        assert settled_after is not None
+        # the search times one configuration per call; the call after the last one settles
+        assert settled_after <= (16 if strategy == b.STRATEGY_FULL else budget)
+        winner = b.sgemm_config_get(M, N, K, 0)
+        assert b.sgemm_space_find(b.SPACE_SMALL, winner) >= 0
+    finally:
+        _restore_cache()
+
+
 def test_launch_on_a_side_stream_and_on_the_set_stream():
     import torch
     cfg = _some_configs()[1]
