@@ -195,6 +195,17 @@ int sgemm_run_config(void *hip_stream, const sgemm_config *cfg, int M, int N, in
                      float alpha, const float *A, int lda, const float *B, int ldb, float beta,
                      float *C, int ldc, int layout);
 
+/* The same with the paper's pre-processing step instead of guarded builds (matrix-multiplication
+ * case study: a "pre-processing kernel" makes the sizes multiples of the tile): A, B and, when
+ * beta != 0, C are copied into zero-padded buffers of a library-owned device workspace whose
+ * sizes are multiples of cfg's tile, the unguarded build runs on those, and the M x N result is
+ * copied back into C.  Same result as sgemm_run_config() within rounding (the padding adds exact
+ * zeros); four extra kernels and (|A| + |B| + 2|C|) of extra traffic.  Sizes that already are
+ * multiples take the ordinary path.  Calls that overlap in time must not both use it. */
+int sgemm_run_config_padded(void *hip_stream, const sgemm_config *cfg, int M, int N, int K,
+                            float alpha, const float *A, int lda, const float *B, int ldb, float beta,
+                            float *C, int ldc, int layout);
+
 /* The reference kernel every tested configuration is compared with inside tune*() (the
  * paper's result verification, section "Advanced usage"): one thread per element of C,
  * products and sums in double, result rounded to float.  Exported so that tests can check it. */

@@ -85,7 +85,7 @@ class tune_result(ctypes.Structure):
 
 EXPORTS = (
     "sgemm_tuned", "sgemm_tuned_on", "sgemm_tuned_online", "sgemm_set_stream", "sgemm_run_config",
-    "sgemm_reference",
+    "sgemm_run_config_padded", "sgemm_reference",
     "tune", "tune_ex", "tune_replay", "sgemm_space_size", "sgemm_space_raw_size",
     "sgemm_space_get", "sgemm_space_find", "sgemm_space_dims", "sgemm_space_values",
     "sgemm_config_check", "sgemm_config_lds_bytes", "sgemm_config_default",
@@ -125,6 +125,7 @@ def lib():
         L.sgemm_tuned_online.argtypes = [vp] + gemm + [i, i, i]
         L.sgemm_set_stream.argtypes = [vp]
         L.sgemm_run_config.argtypes = [vp, cfgp] + gemm
+        L.sgemm_run_config_padded.argtypes = [vp, cfgp] + gemm
         L.sgemm_reference.argtypes = [vp] + gemm
         L.tune.argtypes = [i, i, i, i, i]
         L.tune_ex.argtypes = [i, i, i, i, f, f, i, i, ctypes.c_ulonglong,
@@ -226,6 +227,12 @@ def sgemm_run_config(stream, cfg, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, 
     return _check(lib().sgemm_run_config(_stream(stream), ctypes.byref(cfg), M, N, K, alpha,
                                          _ptr(A), lda, _ptr(B), ldb, beta, _ptr(C), ldc, layout),
                   "sgemm_run_config")
+
+
+def sgemm_run_config_padded(stream, cfg, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, layout=0):
+    return _check(lib().sgemm_run_config_padded(_stream(stream), ctypes.byref(cfg), M, N, K, alpha,
+                                                _ptr(A), lda, _ptr(B), ldb, beta, _ptr(C), ldc,
+                                                layout), "sgemm_run_config_padded")
 
 
 def sgemm_reference(stream, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, layout=0):

@@ -256,6 +256,29 @@ int workspace_for(size_t floats, size_t tiles, float **planes, unsigned int **co
     return SGEMM_OK;
 }
 
+// Second device workspace, for the zero-padded copies of A, B and C of sgemm_run_config_padded().
+float *g_pad_workspace = nullptr;
+size_t g_pad_workspace_floats = 0;
+
+int pad_workspace_for(size_t floats, float **out) {
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (floats > g_pad_workspace_floats) {
+        if (g_pad_workspace) (void)hipFree(g_pad_workspace);
+        g_pad_workspace = nullptr;
+        g_pad_workspace_floats = 0;
+        void *p = nullptr;
+        const hipError_t e = hipMalloc(&p, floats * sizeof(float));
+        if (e != hipSuccess) {
+            set_error(std::string("hipMalloc of the padding workspace: ") + hipGetErrorString(e));
+            return SGEMM_E_LAUNCH;
+        }
+        g_pad_workspace = static_cast<float *>(p);
+        g_pad_workspace_floats = floats;
+    }
+    *out = g_pad_workspace;
+    return SGEMM_OK;
+}
+
 // How the planes of a split-K launch are added up: by default a second kernel does it;
 // SGEMM_TUNED_SPLITK=fused lets the last workgroup of each tile do it inside the GEMM launch
 // (same result bit for bit; measured equally fast, so the simpler way is the default).
@@ -477,6 +500,47 @@ int sgemm_run_config(void *hip_stream, const sgemm_config *cfg, int M, int N, in
     if (!cfg) return SGEMM_E_BADARG;
     return run_config(static_cast<hipStream_t>(hip_stream), *cfg, M, N, K, alpha, A, lda, B, ldb,
                       beta, C, ldc, layout);
+}
+
+int sgemm_run_config_padded(void *hip_stream, const sgemm_config *cfg, int M, int N, int K,
+                            float alpha, const float *A, int lda, const float *B, int ldb, float beta,
+                            float *C, int ldc, int layout) {
+    if (!cfg) return SGEMM_E_BADARG;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    int rc = check_gemm_args(M, N, K, A, lda, B, ldb, C, ldc, layout, alpha != 0.0f);
+    if (rc != SGEMM_OK) return rc;
+    if (violates(*cfg)) return SGEMM_E_INVALID;
+    const int Mp = (M + cfg->mwg - 1) / cfg->mwg * cfg->mwg;
+    const int Np = (N + cfg->nwg - 1) / cfg->nwg * cfg->nwg;
+    const int Kp = (K + cfg->kwg - 1) / cfg->kwg * cfg->kwg;
+    // nothing to pad, or nothing to multiply: the ordinary path
+    if ((Mp == M && Np == N && Kp == K) || M == 0 || N == 0 || K == 0 || alpha == 0.0f)
+        return run_config(s, *cfg, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, layout);
+    const int a_rows = (layout & 1) ? K : M, a_cols = (layout & 1) ? M : K;
+    const int b_rows = (layout & 2) ? N : K, b_cols = (layout & 2) ? K : N;
+    const int ap_rows = (layout & 1) ? Kp : Mp, ap_cols = (layout & 1) ? Mp : Kp;
+    const int bp_rows = (layout & 2) ? Np : Kp, bp_cols = (layout & 2) ? Kp : Np;
+    const size_t na = (size_t)ap_rows * ap_cols, nb = (size_t)bp_rows * bp_cols, nc = (size_t)Mp * Np;
+    float *ws = nullptr;
+    rc = pad_workspace_for(na + nb + nc, &ws);
+    if (rc != SGEMM_OK) return rc;
+    float *Ap = ws, *Bp = ws + na, *Cp = ws + na + nb;
+    hipError_t e = sgemm_util::launch_pad_copy(s, Ap, ap_cols, ap_rows, ap_cols, A, lda, a_rows, a_cols);
+    if (e == hipSuccess) e = sgemm_util::launch_pad_copy(s, Bp, bp_cols, bp_rows, bp_cols, B, ldb, b_rows, b_cols);
+    // C' needs the old C only when beta != 0 (its padding is never copied back)
+    if (e == hipSuccess && beta != 0.0f) e = sgemm_util::launch_pad_copy(s, Cp, Np, Mp, Np, C, ldc, M, N);
+    if (e != hipSuccess) {
+        set_error(std::string("padding copy: ") + hipGetErrorString(e));
+        return SGEMM_E_LAUNCH;
+    }
+    rc = run_config(s, *cfg, Mp, Np, Kp, alpha, Ap, ap_cols, Bp, bp_cols, beta, Cp, Np, layout);
+    if (rc != SGEMM_OK) return rc;
+    e = sgemm_util::launch_copy2d(s, C, ldc, Cp, Np, M, N);
+    if (e != hipSuccess) {
+        set_error(std::string("copy of the result out of the padded buffer: ") + hipGetErrorString(e));
+        return SGEMM_E_LAUNCH;
+    }
+    return SGEMM_OK;
 }
 
 int sgemm_tuned_on(void *hip_stream, int M, int N, int K, float alpha, const float *A, int lda,

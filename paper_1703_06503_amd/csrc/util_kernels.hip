@@ -142,6 +142,19 @@ __global__ void splitk_reduce_kernel(int M, int N, int planes, const float *__re
     }
 }
 
+// dst (rows_d x cols_d, leading dimension ldd) = src (rows_s x cols_s, leading dimension lds_)
+// in its top-left corner, zeros elsewhere: the padding that lets an unguarded GEMM variant
+// run on a problem that is not a multiple of its tile (the paper's pre-processing kernel).
+__global__ void pad_copy_kernel(float *__restrict__ dst, int ldd, int rows_d, int cols_d,
+                                const float *__restrict__ src, int lds_, int rows_s, int cols_s) {
+    const size_t n = (size_t)rows_d * cols_d;
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < n;
+         e += (size_t)gridDim.x * blockDim.x) {
+        const size_t r = e / cols_d, c = e % cols_d;
+        dst[r * ldd + c] = (r < (size_t)rows_s && c < (size_t)cols_s) ? src[r * lds_ + c] : 0.0f;
+    }
+}
+
 __global__ void zero_u32_kernel(unsigned int *p, int n) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = 0u;
@@ -219,6 +232,15 @@ hipError_t launch_splitk_reduce(hipStream_t s, int M, int N, int planes, const f
         hipLaunchKernelGGL(splitk_reduce_kernel<1>, dim3(grid_for(n, 256)), dim3(256), 0, s, M, N,
                            planes, P, plane, alpha, beta, C, ldc);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_pad_copy(hipStream_t s, float *dst, int ldd, int rows_d, int cols_d,
+                           const float *src, int lds_, int rows_s, int cols_s) {
+    const size_t n = (size_t)rows_d * cols_d;
+    if (n == 0) return hipSuccess;
+    hipLaunchKernelGGL(pad_copy_kernel, dim3(grid_for(n, 256)), dim3(256), 0, s, dst, ldd, rows_d,
+                       cols_d, src, lds_, rows_s, cols_s);
     return hipGetLastError();
 }
 

@@ -27,6 +27,8 @@ def run_gpu(cfg, A, B, C, alpha, beta, layout=0, entry="config"):
     lda, ldb, ldc = max(A.shape[1], 1), max(B.shape[1], 1), max(N, 1)
     if entry == "config":
         b.sgemm_run_config(None, cfg, M, N, K, alpha, dA, lda, dB, ldb, beta, dC, ldc, layout)
+    elif entry == "padded":
+        b.sgemm_run_config_padded(None, cfg, M, N, K, alpha, dA, lda, dB, ldb, beta, dC, ldc, layout)
     elif entry == "tuned":
         b.sgemm_tuned_on(None, M, N, K, alpha, dA, lda, dB, ldb, beta, dC, ldc, layout)
     elif entry == "reference":

@@ -26,9 +26,18 @@ def tuned_table_variants():
         b.sgemm_kernel_compile(c, layout, edge)
 
 
+def fixed_config_variants():
+    """The hand-picked configurations of the parity tests, in every layout, guarded and not."""
+    for cfg in t._some_configs():
+        for layout in (0, 1, 2, 3):
+            for edge in (0, 1):
+                b.sgemm_kernel_compile(cfg, layout, edge)
+
+
 def main():
     jobs = min(8, os.cpu_count() or 1)
     tuned_table_variants()
+    fixed_config_variants()
     precompile(b.SPACE_SMALL, (0,), (0,), jobs)
     full = gu.sample_configs(**t.FULL_SAMPLE)
     precompile(b.SPACE_FULL, (0,), (0, 1), jobs, indices=full)

@@ -206,6 +206,30 @@ def _check_leading_dimensions(cfg, M, N, K, lda, ldb, ldc):
     gu.check_against_oracle(out[:M, :N], A, B, C, 1.25, 0.5)
 
 
+@pytest.mark.parametrize("layout", [0, 1, 2, 3])
+@pytest.mark.parametrize("which", [0, 1, 4, 6])
+def test_padded_path_matches_the_oracle_and_leaves_padding_untouched(which, layout):
+    """Pre-processing instead of guards: zero-padded copies, the unguarded build, copy back."""
+    import torch
+    cfg = _some_configs()[which]
+    for shape, (alpha, beta) in [((203, 137, 67), (1.0, 0.0)), ((300, 520, 44), (-1.5, 0.25)),
+                                 ((256, 256, 64), (1.0, 1.0))]:
+        M, N, K = shape
+        A, B, C = synth.make_inputs(M, N, K, layout, seed=76 + layout)
+        got = gu.run_gpu(cfg, A, B, C, alpha, beta, layout, entry="padded")
+        gu.check_against_oracle(got, A, B, C, alpha, beta, layout, what=f"padded {cfg} {shape}")
+    # ld > N: what lies outside M x N is not written
+    M, N, K, ldc = 97, 83, 45, 89
+    A, B, _ = synth.make_inputs(M, N, K, layout, seed=77)
+    Cbuf = np.random.default_rng(78).uniform(-1, 1, (M + 2, ldc)).astype(np.float32)
+    dA, dB, dC = (torch.from_numpy(x).cuda() for x in (A, B, Cbuf.copy()))
+    b.sgemm_run_config_padded(None, cfg, M, N, K, 1.0, dA, A.shape[1], dB, B.shape[1], 0.5, dC, ldc, layout)
+    torch.cuda.synchronize()
+    out = dC.cpu().numpy()
+    assert np.array_equal(out[:M, N:], Cbuf[:M, N:]) and np.array_equal(out[M:], Cbuf[M:])
+    gu.check_against_oracle(out[:M, :N], A, B, Cbuf[:M, :N].copy(), 1.0, 0.5, layout)
+
+
 def test_degenerate_sizes():
     import torch
     cfg = _some_configs()[1]
