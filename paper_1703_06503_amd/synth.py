@@ -1,5 +1,5 @@
-"""Seeded synthetic inputs for the SGEMM workloads.  This module holds no GEMM or tuner
-arithmetic: it only draws matrices.  It is the one module that both the tests' oracle side
+"""Seeded synthetic inputs for the SGEMM workloads (and, at the end, for the 2D convolution).
+This module holds no GEMM, convolution or tuner arithmetic: it only draws matrices.  It is the one module that both the tests' oracle side
 and the GPU side take their inputs from.
 
 Recipe: numpy's PCG64 generator seeded with the workload's seed; matrices are drawn in the
@@ -92,3 +92,38 @@ def sample_positions(M, N, seed, rows=64, cols=64, scattered=4096, edge=128):
     r = np.concatenate(r_list).astype(np.int32)
     c = np.concatenate(c_list).astype(np.int32)
     return r, c
+
+
+# ---- 2D convolution (the paper's first case study) --------------------------------------------
+@dataclass(frozen=True)
+class ConvWorkload:
+    name: str
+    X: int       # output width (fastest index)
+    Y: int       # output height
+    Xf: int      # filter width
+    Yf: int      # filter height
+    w: float     # weighing factor
+    seed: int
+
+
+# The paper's image (8192 by 4096) with its three filter sizes, and a small case.
+CONV_WORKLOADS = {
+    "conv_small_5x5": ConvWorkload("conv_small_5x5", 300, 200, 5, 5, 0.04, 10),
+    "conv_3x3": ConvWorkload("conv_3x3", 8192, 4096, 3, 3, 1.0 / 9, 11),
+    "conv_7x7": ConvWorkload("conv_7x7", 8192, 4096, 7, 7, 1.0 / 49, 12),
+    "conv_11x11": ConvWorkload("conv_11x11", 8192, 4096, 11, 11, 1.0 / 121, 13),
+}
+
+
+def make_conv_inputs(X, Y, Xf, Yf, seed, dist="uniform", lda=None):
+    """The input image WITH its halo, (Y + Yf - 1) x lda float32 with lda >= X + Xf - 1, and the
+    filter, Yf x Xf float32; drawn in that order from PCG64(seed)."""
+    rng = np.random.default_rng(seed)
+    lda = lda or X + Xf - 1
+    A = _draw(rng, (Y + Yf - 1, lda), dist)
+    F = _draw(rng, (Yf, Xf), dist)
+    return A, F
+
+
+def make_conv_workload(w: ConvWorkload):
+    return make_conv_inputs(w.X, w.Y, w.Xf, w.Yf, w.seed)
