@@ -83,6 +83,38 @@ class tune_result(ctypes.Structure):
                 ("reserved", ctypes.c_int * 6)]
 
 
+CONV_FIELDS = ("xwg", "ywg", "xwpt", "ywpt", "lmem", "vw", "pad", "unr")
+
+
+class conv2d_config(ctypes.Structure):
+    """include/conv2d_tuned.h: one configuration of the convolution kernel family."""
+    _fields_ = [(n, ctypes.c_int) for n in CONV_FIELDS]
+
+    def as_tuple(self):
+        return tuple(getattr(self, n) for n in CONV_FIELDS)
+
+    def __repr__(self):
+        return "conv2d_config(" + ", ".join(f"{n}={getattr(self, n)}" for n in CONV_FIELDS) + ")"
+
+
+def make_conv_config(*args):
+    if len(args) != len(CONV_FIELDS):
+        raise ValueError("expected %d values" % len(CONV_FIELDS))
+    c = conv2d_config()
+    for n, v in zip(CONV_FIELDS, args):
+        setattr(c, n, int(v))
+    return c
+
+
+class conv2d_tune_result(ctypes.Structure):
+    _fields_ = [("best", conv2d_config), ("best_ms", ctypes.c_float),
+                ("best_gflops", ctypes.c_float), ("best_gbs", ctypes.c_float),
+                ("best_index", ctypes.c_int), ("evaluations", ctypes.c_int),
+                ("failed", ctypes.c_int), ("space_size", ctypes.c_int),
+                ("evals_to_best", ctypes.c_int), ("total_ms", ctypes.c_float),
+                ("compile_ms", ctypes.c_float), ("reserved", ctypes.c_int * 4)]
+
+
 EXPORTS = (
     "sgemm_tuned", "sgemm_tuned_on", "sgemm_tuned_online", "sgemm_set_stream", "sgemm_run_config",
     "sgemm_run_config_padded", "sgemm_reference",
@@ -95,6 +127,11 @@ EXPORTS = (
     "sgemm_config_set", "sgemm_config_select", "sgemm_cache_load", "sgemm_cache_save",
     "sgemm_cache_clear", "sgemm_cache_count", "sgemm_device_peak", "sgemm_status_string",
     "sgemm_last_error",
+    # include/conv2d_tuned.h
+    "conv2d_space_size", "conv2d_space_get", "conv2d_space_find", "conv2d_config_check",
+    "conv2d_config_lds_bytes", "conv2d_config_threads", "conv2d_kernel_compile",
+    "conv2d_run_config", "conv2d_reference", "conv2d_tuned", "conv2d_config_set",
+    "conv2d_config_select", "conv2d_tune", "conv2d_tune_replay",
 )
 
 _lib = None
@@ -158,6 +195,25 @@ def lib():
         L.sgemm_status_string.restype = ctypes.c_char_p
         L.sgemm_last_error.argtypes = []
         L.sgemm_last_error.restype = ctypes.c_char_p
+        ccfgp = ctypes.POINTER(conv2d_config)
+        conv = [i, i, i, i, f, vp, vp, i, vp, i]      # X Y Xf Yf w F A lda B ldb
+        L.conv2d_space_size.argtypes = [i, i]
+        L.conv2d_space_get.argtypes = [i, i, i, ccfgp]
+        L.conv2d_space_find.argtypes = [i, i, ccfgp]
+        L.conv2d_config_check.argtypes = [ccfgp, i, i]
+        L.conv2d_config_lds_bytes.argtypes = [ccfgp, i, i]
+        L.conv2d_config_threads.argtypes = [ccfgp, i, i]
+        L.conv2d_kernel_compile.argtypes = [ccfgp, i, i, i, i, ctypes.POINTER(sgemm_kernel_info)]
+        L.conv2d_run_config.argtypes = [vp, ccfgp] + conv
+        L.conv2d_reference.argtypes = [vp] + conv
+        L.conv2d_tuned.argtypes = conv
+        L.conv2d_config_set.argtypes = [i, i, i, i, ccfgp, f]
+        L.conv2d_config_select.argtypes = [i, i, i, i, ccfgp]
+        L.conv2d_tune.argtypes = [i, i, i, i, f, i, i, ctypes.c_ulonglong,
+                                  ctypes.POINTER(tune_opts), ctypes.POINTER(conv2d_tune_result)]
+        L.conv2d_tune_replay.argtypes = [i, i, ctypes.POINTER(f), i, i, i, ctypes.c_ulonglong,
+                                         ctypes.POINTER(tune_opts), ctypes.POINTER(i), i,
+                                         ctypes.POINTER(conv2d_tune_result)]
         _lib = L
     return _lib
 
@@ -385,3 +441,84 @@ def sgemm_device_peak():
     _check(lib().sgemm_device_peak(ctypes.byref(g), ctypes.byref(cu), ctypes.byref(mhz)),
            "sgemm_device_peak")
     return g.value, cu.value, mhz.value
+
+
+# ---- include/conv2d_tuned.h -----------------------------------------------------------------
+def conv2d_space_size(Xf, Yf):
+    return _check(lib().conv2d_space_size(Xf, Yf), "conv2d_space_size")
+
+
+def conv2d_space_get(Xf, Yf, index):
+    c = conv2d_config()
+    _check(lib().conv2d_space_get(Xf, Yf, index, ctypes.byref(c)), "conv2d_space_get")
+    return c
+
+
+def conv2d_space_find(Xf, Yf, cfg):
+    return lib().conv2d_space_find(Xf, Yf, ctypes.byref(cfg))
+
+
+def conv2d_config_check(cfg, Xf, Yf):
+    return lib().conv2d_config_check(ctypes.byref(cfg), Xf, Yf)
+
+
+def conv2d_config_lds_bytes(cfg, Xf, Yf):
+    return _check(lib().conv2d_config_lds_bytes(ctypes.byref(cfg), Xf, Yf), "conv2d_config_lds_bytes")
+
+
+def conv2d_config_threads(cfg, Xf, Yf):
+    return _check(lib().conv2d_config_threads(ctypes.byref(cfg), Xf, Yf), "conv2d_config_threads")
+
+
+def conv2d_kernel_compile(cfg, Xf, Yf, edge=0, vector=1):
+    info = sgemm_kernel_info()
+    _check(lib().conv2d_kernel_compile(ctypes.byref(cfg), Xf, Yf, edge, vector, ctypes.byref(info)),
+           "conv2d_kernel_compile")
+    return info
+
+
+def conv2d_run_config(stream, cfg, X, Y, Xf, Yf, w, F, A, lda, B, ldb):
+    return _check(lib().conv2d_run_config(_stream(stream), ctypes.byref(cfg), X, Y, Xf, Yf, w,
+                                          _ptr(F), _ptr(A), lda, _ptr(B), ldb), "conv2d_run_config")
+
+
+def conv2d_reference(stream, X, Y, Xf, Yf, w, F, A, lda, B, ldb):
+    return _check(lib().conv2d_reference(_stream(stream), X, Y, Xf, Yf, w, _ptr(F), _ptr(A), lda,
+                                         _ptr(B), ldb), "conv2d_reference")
+
+
+def conv2d_tuned(X, Y, Xf, Yf, w, F, A, lda, B, ldb):
+    return _check(lib().conv2d_tuned(X, Y, Xf, Yf, w, _ptr(F), _ptr(A), lda, _ptr(B), ldb),
+                  "conv2d_tuned")
+
+
+def conv2d_config_set(X, Y, Xf, Yf, cfg, ms=0.0):
+    return _check(lib().conv2d_config_set(X, Y, Xf, Yf, ctypes.byref(cfg), ms), "conv2d_config_set")
+
+
+def conv2d_config_select(X, Y, Xf, Yf):
+    """Returns (exact, conv2d_config)."""
+    c = conv2d_config()
+    exact = _check(lib().conv2d_config_select(X, Y, Xf, Yf, ctypes.byref(c)), "conv2d_config_select")
+    return exact, c
+
+
+def conv2d_tune(X, Y, Xf, Yf, w, strategy, budget, seed=0, opts=None):
+    """Returns (evaluations, conv2d_tune_result)."""
+    res = conv2d_tune_result()
+    n = _check(lib().conv2d_tune(X, Y, Xf, Yf, w, strategy, budget, seed,
+                                 ctypes.byref(opts) if opts is not None else None,
+                                 ctypes.byref(res)), "conv2d_tune")
+    return n, res
+
+
+def conv2d_tune_replay(Xf, Yf, ms_table, strategy, budget, seed=0, opts=None):
+    """Returns (evaluations, conv2d_tune_result, visited indices)."""
+    n = len(ms_table)
+    table = (ctypes.c_float * n)(*ms_table)
+    visited = (ctypes.c_int * n)()
+    res = conv2d_tune_result()
+    ev = _check(lib().conv2d_tune_replay(Xf, Yf, table, n, strategy, budget, seed,
+                                         ctypes.byref(opts) if opts is not None else None,
+                                         visited, n, ctypes.byref(res)), "conv2d_tune_replay")
+    return ev, res, list(visited[:ev])

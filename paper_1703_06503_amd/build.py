@@ -9,7 +9,7 @@ LIBDIR = os.path.join(HERE, "lib")
 OBJDIR = os.path.join(LIBDIR, "obj")
 LIB = os.path.join(LIBDIR, "libsgemm_tuned.so")
 HIP_SOURCES = ["util_kernels.hip"]
-CPP_SOURCES = ["library.cpp", "space.cpp", "strategy.cpp", "kernelgen.cpp"]
+CPP_SOURCES = ["library.cpp", "space.cpp", "strategy.cpp", "kernelgen.cpp", "conv.cpp"]
 ROCM = os.environ.get("ROCM_PATH", "/opt/rocm")
 HIPCC = os.path.join(ROCM, "bin", "hipcc")
 # packed-FP32 instructions are kept out of all device code
@@ -32,6 +32,7 @@ def _run(cmd, verbose):
 def build(verbose: bool = False) -> str:
     os.makedirs(OBJDIR, exist_ok=True)
     kernel_src = os.path.join(CSRC, "sgemm_kernel.hip.inc")
+    conv_src = os.path.join(CSRC, "conv_kernel.hip.inc")
     objs = []
     for s in HIP_SOURCES:
         o = os.path.join(OBJDIR, s + ".o")
@@ -42,6 +43,7 @@ def build(verbose: bool = False) -> str:
         o = os.path.join(OBJDIR, s + ".o")
         _run([HIPCC, "-x", "c++", "-D__HIP_PLATFORM_AMD__", "-O2", "-std=c++17", "-fPIC", "-Wall",
               f"-I{ROCM}/include", f'-DSGEMM_KERNEL_SOURCE_PATH="{kernel_src}"',
+              f'-DCONV_KERNEL_SOURCE_PATH="{conv_src}"',
               "-c", os.path.join(CSRC, s), "-o", o], verbose)
         objs.append(o)
     # link beside the target and rename over it: a process that has the old library mapped

@@ -22,6 +22,16 @@ __asm__(".section .rodata\n"
         ".previous\n");
 extern "C" const char sgemm_kernel_source_begin[];
 extern "C" const char sgemm_kernel_source_end[];
+__asm__(".section .rodata\n"
+        ".global conv_kernel_source_begin\n"
+        "conv_kernel_source_begin:\n"
+        ".incbin \"" CONV_KERNEL_SOURCE_PATH "\"\n"
+        ".global conv_kernel_source_end\n"
+        "conv_kernel_source_end:\n"
+        ".byte 0\n"
+        ".previous\n");
+extern "C" const char conv_kernel_source_begin[];
+extern "C" const char conv_kernel_source_end[];
 
 namespace sgemm {
 
@@ -153,42 +163,57 @@ void read_code_object_info(const std::vector<char> &image, sgemm_kernel_info *in
 // The kernel source with comments removed, runs of blanks collapsed and blank lines dropped:
 // what the cache key is computed from, so that rewording a comment does not invalidate every
 // cached variant.  Line breaks are kept (they end preprocessor directives).
-const std::string &normalized_source() {
-    static const std::string text = [] {
-        const char *p = sgemm_kernel_source_begin, *end = sgemm_kernel_source_end;
-        std::string out;
-        out.reserve((size_t)(end - p));
-        int gap = 0; // 0 = none, 1 = blanks, 2 = at least one line break
-        while (p < end) {
-            if (p + 1 < end && p[0] == '/' && p[1] == '/') {
-                while (p < end && *p != '\n') ++p;
-            } else if (p + 1 < end && p[0] == '/' && p[1] == '*') {
-                p += 2;
-                while (p + 1 < end && !(p[0] == '*' && p[1] == '/')) ++p;
-                p = (p + 1 < end) ? p + 2 : end;
-                if (gap < 1) gap = 1;
-            } else if (*p == '\n') {
-                gap = 2;
-                ++p;
-            } else if (*p == ' ' || *p == '\t' || *p == '\r') {
-                if (gap < 1) gap = 1;
-                ++p;
-            } else {
-                if (gap && !out.empty()) out.push_back(gap == 2 ? '\n' : ' ');
-                gap = 0;
-                out.push_back(*p++);
-            }
+std::string normalize(const char *p, const char *end) {
+    std::string out;
+    out.reserve((size_t)(end - p));
+    int gap = 0; // 0 = none, 1 = blanks, 2 = at least one line break
+    while (p < end) {
+        if (p + 1 < end && p[0] == '/' && p[1] == '/') {
+            while (p < end && *p != '\n') ++p;
+        } else if (p + 1 < end && p[0] == '/' && p[1] == '*') {
+            p += 2;
+            while (p + 1 < end && !(p[0] == '*' && p[1] == '/')) ++p;
+            p = (p + 1 < end) ? p + 2 : end;
+            if (gap < 1) gap = 1;
+        } else if (*p == '\n') {
+            gap = 2;
+            ++p;
+        } else if (*p == ' ' || *p == '\t' || *p == '\r') {
+            if (gap < 1) gap = 1;
+            ++p;
+        } else {
+            if (gap && !out.empty()) out.push_back(gap == 2 ? '\n' : ' ');
+            gap = 0;
+            out.push_back(*p++);
         }
-        return out;
-    }();
-    return text;
+    }
+    return out;
+}
+
+const std::string &normalized_source(const KernelSource &src) {
+    static const std::string gemm = normalize(sgemm_kernel_source_begin, sgemm_kernel_source_end);
+    static const std::string conv = normalize(conv_kernel_source_begin, conv_kernel_source_end);
+    return src.begin == sgemm_kernel_source_begin ? gemm : conv;
+}
+
+const KernelSource &gemm_source() {
+    static const KernelSource s{sgemm_kernel_source_begin, sgemm_kernel_source_end, "sgemm_variant.hip",
+                                "sgemm_variant"};
+    return s;
+}
+
+const KernelSource &conv_source() {
+    static const KernelSource s{conv_kernel_source_begin, conv_kernel_source_end, "conv2d_variant.hip",
+                                "conv2d_variant"};
+    return s;
 }
 
 // File of a variant's code object in the cache directory: a hash of the kernel source (without
 // comments), the macros, the compiler flags, any experiment defines and the compiler's identity.
-std::string code_object_path(const VariantKey &key) {
-    const std::string macros = key.macros();
-    const std::string &src = normalized_source();
+std::string code_object_path(const VariantKey &key) { return code_object_path(gemm_source(), key.macros()); }
+
+std::string code_object_path(const KernelSource &source, const std::string &macros) {
+    const std::string &src = normalized_source(source);
     uint64_t h = fnv1a(src.data(), src.size());
     h = fnv1a(macros.data(), macros.size(), h);
     for (const char *f : kCompilerFlags) h = fnv1a(f, std::strlen(f), h);
@@ -203,10 +228,14 @@ std::string code_object_path(const VariantKey &key) {
 }
 
 int get_code_object(const VariantKey &key, CodeObject *out, std::string *log) {
-    const std::string macros = key.macros();
+    return get_code_object(gemm_source(), key.macros(), out, log);
+}
+
+int get_code_object(const KernelSource &source, const std::string &macros, CodeObject *out,
+                    std::string *log) {
     const char *extra_env = std::getenv("SGEMM_TUNED_EXTRA_DEFINES");
     const std::string extra = extra_env ? extra_env : "";
-    const std::string path = code_object_path(key);
+    const std::string path = code_object_path(source, macros);
     const std::string dir = cache_dir();
 
     out->info = sgemm_kernel_info{};
@@ -242,7 +271,7 @@ int get_code_object(const VariantKey &key, CodeObject *out, std::string *log) {
     for (auto &o : opts) argv.push_back(o.c_str());
 
     hiprtcProgram prog = nullptr;
-    if (hiprtcCreateProgram(&prog, sgemm_kernel_source_begin, "sgemm_variant.hip", 0, nullptr,
+    if (hiprtcCreateProgram(&prog, source.begin, source.file_name, 0, nullptr,
                             nullptr) != HIPRTC_SUCCESS) {
         if (log) *log = "hiprtcCreateProgram failed";
         return SGEMM_E_COMPILE;
@@ -279,19 +308,24 @@ LoadedKernel::~LoadedKernel() {
 }
 
 int load_kernel(const VariantKey &key, std::shared_ptr<LoadedKernel> *out, std::string *log) {
+    return load_kernel(gemm_source(), key.macros(), key.cfg.mdimc * key.cfg.ndimc, out, log);
+}
+
+int load_kernel(const KernelSource &source, const std::string &macros, int threads,
+                std::shared_ptr<LoadedKernel> *out, std::string *log) {
     CodeObject co;
-    const int rc = get_code_object(key, &co, log);
+    const int rc = get_code_object(source, macros, &co, log);
     if (rc != SGEMM_OK) return rc;
     auto k = std::make_shared<LoadedKernel>();
     k->info = co.info;
-    k->threads = key.cfg.mdimc * key.cfg.ndimc;
+    k->threads = threads;
     hipError_t e = hipModuleLoadData(&k->module, co.image.data());
     if (e != hipSuccess) {
-        if (log) *log = std::string("hipModuleLoadData: ") + hipGetErrorString(e) + " [" + key.macros() + "]";
+        if (log) *log = std::string("hipModuleLoadData: ") + hipGetErrorString(e) + " [" + macros + "]";
         k->module = nullptr;
         return SGEMM_E_LAUNCH;
     }
-    e = hipModuleGetFunction(&k->fn, k->module, "sgemm_variant");
+    e = hipModuleGetFunction(&k->fn, k->module, source.entry);
     if (e != hipSuccess) {
         if (log) *log = std::string("hipModuleGetFunction: ") + hipGetErrorString(e);
         return SGEMM_E_LAUNCH;

@@ -23,6 +23,15 @@ struct VariantKey {
     std::string macros() const; // "-DMWG=.. -DNWG=.. ..." in a fixed order
 };
 
+// A kernel family's source text as it travels inside the library, and its entry point.
+struct KernelSource {
+    const char *begin, *end;
+    const char *file_name; // name shown in compiler messages
+    const char *entry;
+};
+const KernelSource &gemm_source(); // sgemm_kernel.hip.inc
+const KernelSource &conv_source(); // conv_kernel.hip.inc
+
 struct CodeObject {
     std::vector<char> image;
     sgemm_kernel_info info{};
@@ -34,6 +43,11 @@ int get_code_object(const VariantKey &key, CodeObject *out, std::string *log);
 
 // Where the variant's code object is (or will be) kept in the cache directory.
 std::string code_object_path(const VariantKey &key);
+
+// The same three steps for any kernel family: `macros` is its "-DNAME=value ..." string.
+int get_code_object(const KernelSource &source, const std::string &macros, CodeObject *out,
+                    std::string *log);
+std::string code_object_path(const KernelSource &source, const std::string &macros);
 
 void set_cache_dir(const std::string &path);
 std::string cache_dir();
@@ -48,6 +62,8 @@ struct LoadedKernel {
 };
 
 int load_kernel(const VariantKey &key, std::shared_ptr<LoadedKernel> *out, std::string *log);
+int load_kernel(const KernelSource &source, const std::string &macros, int threads,
+                std::shared_ptr<LoadedKernel> *out, std::string *log);
 
 // Reads vgpr/agpr/sgpr counts and LDS/scratch sizes from a code object's metadata note.
 void read_code_object_info(const std::vector<char> &image, sgemm_kernel_info *info);

@@ -20,21 +20,18 @@
 #include <vector>
 
 #include "../../include/sgemm_tuned.h"
+#include "internal.h"
 #include "kernelgen.h"
 #include "space.h"
 #include "strategy.h"
 #include "util_kernels.h"
 
 using namespace sgemm;
+using namespace sgemm::detail;
 
 namespace {
 
 thread_local std::string t_last_error; // detail of the calling thread's last failure
-
-void set_error(const std::string &what) {
-    t_last_error = what;
-    if (std::getenv("SGEMM_TUNED_VERBOSE")) std::fprintf(stderr, "sgemm_tuned: %s\n", what.c_str());
-}
 
 std::mutex g_mu;                  // guards everything below
 hipStream_t g_stream = nullptr;   // stream of sgemm_tuned()
@@ -387,20 +384,6 @@ int run_config(hipStream_t s, const sgemm_config &cfg, int M, int N, int K, floa
     return launch_loaded(s, *k, key.cfg, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc);
 }
 
-StrategyParams params_from(const tune_opts *o) {
-    StrategyParams p;
-    if (!o) return p;
-    if (o->sa_T > 0) p.sa_T = o->sa_T;
-    p.sa_raw_ms = o->sa_raw_ms != 0;
-    if (o->pso_S > 0) p.pso_S = o->pso_S;
-    if (o->pso_alpha != 0 || o->pso_beta != 0 || o->pso_gamma != 0) {
-        p.pso_alpha = o->pso_alpha; p.pso_beta = o->pso_beta; p.pso_gamma = o->pso_gamma;
-    }
-    if (o->random_fraction > 0) p.random_fraction = o->random_fraction;
-    if (o->warm_start < 0) p.start_index = -o->warm_start - 1;
-    return p;
-}
-
 void fill_result(const Space &space, const SearchResult &r, double flops, tune_result *out) {
     if (!out) return;
     *out = tune_result{};
@@ -415,19 +398,6 @@ void fill_result(const Space &space, const SearchResult &r, double flops, tune_r
         out->best_gflops = (float)(flops / (r.best_cost * 1e-3) * 1e-9);
     }
 }
-
-struct DeviceBuffer {
-    void *p = nullptr;
-    ~DeviceBuffer() { if (p) (void)hipFree(p); }
-    hipError_t alloc(size_t bytes) { return hipMalloc(&p, bytes ? bytes : 4); }
-    float *f() const { return static_cast<float *>(p); }
-};
-
-struct Event {
-    hipEvent_t e = nullptr;
-    Event() { (void)hipEventCreate(&e); }
-    ~Event() { if (e) (void)hipEventDestroy(e); }
-};
 
 // ---- on-line tuning ------------------------------------------------------------------------
 // The paper also proposes tuning at run time, in the first calls of an application ("CLTune:
@@ -460,13 +430,88 @@ struct OnlineSearch {
 std::mutex g_online_mu;
 std::map<std::tuple<int, int, int, int, int>, std::unique_ptr<OnlineSearch>> g_online; // + space
 
+} // namespace
+
+namespace sgemm {
+namespace detail {
+
+void set_error(const std::string &what) {
+    t_last_error = what;
+    if (std::getenv("SGEMM_TUNED_VERBOSE")) std::fprintf(stderr, "sgemm_tuned: %s\n", what.c_str());
+}
+
+hipStream_t library_stream() {
+    std::lock_guard<std::mutex> lock(g_mu);
+    return g_stream;
+}
+
 double median(std::vector<double> v) {
     std::sort(v.begin(), v.end());
     const size_t n = v.size();
     return n % 2 ? v[n / 2] : 0.5 * (v[n / 2 - 1] + v[n / 2]);
 }
 
-} // namespace
+StrategyParams params_from(const tune_opts *o) {
+    StrategyParams p;
+    if (!o) return p;
+    if (o->sa_T > 0) p.sa_T = o->sa_T;
+    p.sa_raw_ms = o->sa_raw_ms != 0;
+    if (o->pso_S > 0) p.pso_S = o->pso_S;
+    if (o->pso_alpha != 0 || o->pso_beta != 0 || o->pso_gamma != 0) {
+        p.pso_alpha = o->pso_alpha; p.pso_beta = o->pso_beta; p.pso_gamma = o->pso_gamma;
+    }
+    if (o->random_fraction > 0) p.random_fraction = o->random_fraction;
+    if (o->warm_start < 0) p.start_index = -o->warm_start - 1;
+    return p;
+}
+
+TimingRules timing_rules_from(const tune_opts *o) {
+    TimingRules r;
+    if (o && o->warmup > 0) r.warmup = o->warmup;
+    if (o && o->reps > 0) r.reps = o->reps;
+    if (o && o->cut_factor != 0.0f) r.cut = o->cut_factor;
+    if (o && o->warmup_ms != 0.0f) r.warmup_ms = o->warmup_ms;
+    return r;
+}
+
+double time_configuration(hipStream_t s, const std::function<void()> &launch, float first,
+                          const TimingRules &rules, double best_ms, Event &ev0, Event &ev1,
+                          int *samples, bool *was_cut) {
+    *was_cut = false;
+    // `first` is the duration of the verified launch: cold clocks, up to ~1.25x slow
+    if (rules.cut > 0.0 && best_ms > 0.0 && first > 1.3 * rules.cut * best_ms) {
+        *samples = 1; // hopeless even allowing for the cold start: not worth warming up
+        *was_cut = true;
+        return first;
+    }
+    int warm = rules.warmup - 1;
+    if (rules.warmup_ms > 0.0 && first > 0.0f)
+        warm = std::max(warm, std::min(4096, (int)std::ceil(rules.warmup_ms / first)));
+    for (int w = 0; w < warm; ++w) launch();
+    // short kernels: several launches per sample so that a sample lasts >= 0.2 ms
+    int batch = 1;
+    if (first > 0.0f && first < 0.2f) batch = std::min(64, (int)std::ceil(0.2f / first));
+    std::vector<double> t;
+    for (int r = 0; r < rules.reps; ++r) {
+        (void)hipEventRecord(ev0.e, s);
+        for (int b = 0; b < batch; ++b) launch();
+        (void)hipEventRecord(ev1.e, s);
+        if (hipEventSynchronize(ev1.e) != hipSuccess) return -1.0;
+        float e = 0.0f;
+        (void)hipEventElapsedTime(&e, ev0.e, ev1.e);
+        t.push_back((double)e / batch);
+        if (r == 0 && rules.cut > 0.0 && best_ms > 0.0 && t[0] > rules.cut * best_ms) {
+            *was_cut = true;
+            break;
+        }
+    }
+    if (t.empty()) return -1.0;
+    *samples = (int)t.size();
+    return median(t);
+}
+
+} // namespace detail
+} // namespace sgemm
 
 extern "C" {
 
@@ -885,11 +930,8 @@ int tune_ex(int M, int N, int K, int layout, float alpha, float beta, int strate
     const Space *space = get_space(opts ? opts->space : SGEMM_SPACE_FULL);
     if (!space) return SGEMM_E_BADARG;
     if (space->configs.empty()) return SGEMM_E_NOCONFIG;
-    const int warmup = (opts && opts->warmup > 0) ? opts->warmup : 2;
-    const int reps = (opts && opts->reps > 0) ? opts->reps : 7;
+    const TimingRules rules = timing_rules_from(opts);
     const bool verify = !(opts && opts->verify_off);
-    const double cut = (opts && opts->cut_factor != 0.0f) ? opts->cut_factor : 3.0;
-    const double warmup_ms = (opts && opts->warmup_ms != 0.0f) ? opts->warmup_ms : 25.0;
 
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) return SGEMM_E_NODEVICE;
@@ -987,36 +1029,13 @@ int tune_ex(int M, int N, int K, int layout, float alpha, float beta, int strate
             if (verify) (void)hipMemcpyAsync(bits, dwords, 8, hipMemcpyDeviceToHost, s);
             if (hipStreamSynchronize(s) != hipSuccess) { status = "fault"; hip_failure = 1; break; }
             if (verify && bits[0] != 0) { status = "verify"; break; }
-            float first = 0.0f; // duration of the verified launch: cold clocks, up to ~1.25x slow
+            float first = 0.0f;
             (void)hipEventElapsedTime(&first, ev0.e, ev1.e);
-            if (cut > 0.0 && best_ms > 0.0 && first > 1.3 * cut * best_ms) {
-                ms = first; // hopeless even allowing for the cold start: not worth warming up
-                samples = 1;
-                status = "ok-cut";
-                break;
-            }
-            int warm = warmup - 1;
-            if (warmup_ms > 0.0 && first > 0.0f)
-                warm = std::max(warm, std::min(4096, (int)std::ceil(warmup_ms / first)));
-            for (int w = 0; w < warm; ++w) launch();
-            // short kernels: several launches per sample so that a sample lasts >= 0.2 ms
-            int batch = 1;
-            if (first > 0.0f && first < 0.2f) batch = std::min(64, (int)std::ceil(0.2f / first));
-            std::vector<double> t;
-            bool failed = false;
-            for (int r = 0; r < reps; ++r) {
-                (void)hipEventRecord(ev0.e, s);
-                for (int b = 0; b < batch; ++b) launch();
-                (void)hipEventRecord(ev1.e, s);
-                if (hipEventSynchronize(ev1.e) != hipSuccess) { failed = true; break; }
-                float e = 0.0f;
-                (void)hipEventElapsedTime(&e, ev0.e, ev1.e);
-                t.push_back((double)e / batch);
-                if (r == 0 && cut > 0.0 && best_ms > 0.0 && t[0] > cut * best_ms) { status = "ok-cut"; break; }
-            }
-            if (failed || t.empty()) { status = "fault"; hip_failure = 1; break; }
-            samples = (int)t.size();
-            ms = median(t);
+            bool was_cut = false;
+            ms = time_configuration(s, [&] { (void)launch(); }, first, rules, best_ms, ev0, ev1, &samples,
+                                    &was_cut);
+            if (ms < 0.0) { status = "fault"; hip_failure = 1; break; }
+            if (was_cut) { status = "ok-cut"; break; }
             if (best_ms == 0.0 || ms < best_ms) best_ms = ms;
         } while (false);
         if (logf) {

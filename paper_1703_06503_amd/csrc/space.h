@@ -36,6 +36,7 @@ const char *violates(const sgemm_config &c);
 
 struct Space {
     int preset = -1;
+    int dims = kDims;                     // leading entries of a Point that are parameters
     std::vector<std::vector<int>> values; // per dimension
     std::vector<Point> configs;           // valid points, lexicographic in dimension order
     std::unordered_map<uint64_t, int> index;

@@ -16,7 +16,7 @@ uint64_t Rng::next() {
 std::vector<int> neighbours(const Space &space, int index) {
     std::vector<int> out;
     const Point &cur = space.configs[index];
-    for (int d = 0; d < kDims; ++d) {
+    for (int d = 0; d < space.dims; ++d) {
         for (int v : space.values[d]) {
             if (v == cur[d]) continue;
             Point p = cur;
@@ -128,8 +128,8 @@ void particle_swarm(Evaluator &ev, const Space &space, Rng &rng, const StrategyP
         for (int i = 0; i < S && ev.res.evaluations < ev.budget && step < max_steps; ++i, ++step) {
             int next = -1;
             for (int attempt = 0; attempt < 10 && next < 0; ++attempt) {
-                Point q;
-                for (int d = 0; d < kDims; ++d) {
+                Point q{}; // entries beyond space.dims stay zero, as in every stored point
+                for (int d = 0; d < space.dims; ++d) {
                     const double u = rng.uniform();
                     if (u < p.pso_alpha) {
                         q[d] = space.values[d][rng.below(space.values[d].size())];

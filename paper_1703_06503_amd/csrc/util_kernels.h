@@ -23,6 +23,9 @@ hipError_t launch_compare(hipStream_t s, const float *got, int ldg, const float 
 // C = alpha * (P[0] + ... + P[planes-1]) + beta * C; P[s] = M x N floats (ld N) at P + s*plane.
 hipError_t launch_splitk_reduce(hipStream_t s, int M, int N, int planes, const float *P,
                                 size_t plane, float alpha, float beta, float *C, int ldc);
+// B[y][x] = w * sum_j sum_i F[j][i] * A[y+j][x+i]; A holds the halo.
+hipError_t launch_conv2d_reference(hipStream_t s, int X, int Y, int Xf, int Yf, float w, const float *F,
+                                   const float *A, int lda, float *B, int ldb);
 // dst (rows_d x cols_d) = src (rows_s x cols_s) in the top-left corner, zeros elsewhere.
 hipError_t launch_pad_copy(hipStream_t s, float *dst, int ldd, int rows_d, int cols_d,
                            const float *src, int lds_, int rows_s, int cols_s);

@@ -155,6 +155,20 @@ __global__ void pad_copy_kernel(float *__restrict__ dst, int ldd, int rows_d, in
     }
 }
 
+// The convolution every tuned variant is compared with: one thread per output, taps added in
+// the order j outer, i inner (paper: "Case-study: 2D convolution", the equation for B[x,y]).
+__global__ void conv2d_reference_kernel(int X, int Y, int Xf, int Yf, float w,
+                                        const float *__restrict__ F, const float *__restrict__ A,
+                                        int lda, float *__restrict__ B, int ldb) {
+    const int x = blockIdx.x * blockDim.x + threadIdx.x;
+    const int y = blockIdx.y * blockDim.y + threadIdx.y;
+    if (x >= X || y >= Y) return;
+    float acc = 0.0f;
+    for (int j = 0; j < Yf; ++j)
+        for (int i = 0; i < Xf; ++i) acc = fmaf(F[j * Xf + i], A[(size_t)(y + j) * lda + x + i], acc);
+    B[(size_t)y * ldb + x] = w * acc;
+}
+
 __global__ void zero_u32_kernel(unsigned int *p, int n) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = 0u;
@@ -232,6 +246,15 @@ hipError_t launch_splitk_reduce(hipStream_t s, int M, int N, int planes, const f
         hipLaunchKernelGGL(splitk_reduce_kernel<1>, dim3(grid_for(n, 256)), dim3(256), 0, s, M, N,
                            planes, P, plane, alpha, beta, C, ldc);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_conv2d_reference(hipStream_t s, int X, int Y, int Xf, int Yf, float w, const float *F,
+                                   const float *A, int lda, float *B, int ldb) {
+    if (X <= 0 || Y <= 0) return hipSuccess;
+    const dim3 block(64, 4);
+    hipLaunchKernelGGL(conv2d_reference_kernel, dim3((X + 63) / 64, (Y + 3) / 4), block, 0, s, X, Y,
+                       Xf, Yf, w, F, A, lda, B, ldb);
     return hipGetLastError();
 }
 

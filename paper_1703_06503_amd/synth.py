@@ -126,4 +126,5 @@ def make_conv_inputs(X, Y, Xf, Yf, seed, dist="uniform", lda=None):
 
 
 def make_conv_workload(w: ConvWorkload):
-    return make_conv_inputs(w.X, w.Y, w.Xf, w.Yf, w.seed)
+    """Rows of the stored image are padded to a multiple of 16 floats (64-byte aligned rows)."""
+    return make_conv_inputs(w.X, w.Y, w.Xf, w.Yf, w.seed, lda=(w.X + w.Xf - 1 + 15) // 16 * 16)

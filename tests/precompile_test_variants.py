@@ -34,10 +34,28 @@ def fixed_config_variants():
                 b.sgemm_kernel_compile(cfg, layout, edge)
 
 
+def conv_variants():
+    """The convolution variants of tests/test_gpu_conv.py: guarded and unguarded, with and
+    without vector accesses (which of the four a call uses depends on sizes and alignment)."""
+    from tests import test_gpu_conv as tc
+    todo = []
+    for (Xf, Yf) in tc.SAMPLES:
+        todo += [(b.conv2d_space_get(Xf, Yf, i), Xf, Yf) for i in tc.sample(Xf, Yf)]
+    for c in tc.CONFIGS:
+        todo += [(b.make_conv_config(*c), f[0], f[1]) for f in ((7, 5), (3, 3))]
+    for f in (3, 5, 7, 11):
+        todo.append((b.conv2d_config_select(1, 1, f, f)[1], f, f))
+    for cfg, Xf, Yf in todo:
+        for edge in (0, 1):
+            for vector in (0, 1):
+                b.conv2d_kernel_compile(cfg, Xf, Yf, edge, vector)
+
+
 def main():
     jobs = min(8, os.cpu_count() or 1)
     tuned_table_variants()
     fixed_config_variants()
+    conv_variants()
     precompile(b.SPACE_SMALL, (0,), (0,), jobs)
     full = gu.sample_configs(**t.FULL_SAMPLE)
     precompile(b.SPACE_FULL, (0,), (0, 1), jobs, indices=full)
