@@ -3,6 +3,9 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--tune-budget B] [--workload NAME]
 
+(--workload conv_3x3 / conv_7x7 / conv_11x11 times the library's second kernel family, the tunable
+2D convolution, in the same way and prints the same kind of line; see conv_main.)
+
 One step = one sgemm_tuned() call on the resident synthetic operands of the workload: the
 per-shape cache lookup, variant dispatch and the generated kernel (workgroup tiling, LDS
 staging, MFMA inner product, epilogue).  Before the timed region the tuner itself runs on the
@@ -40,6 +43,10 @@ MEASURED_TRAFFIC_BYTES = {
     ("cfg1_256", (64, 32, 1, 1)): (2.30 + 0.25) * 2 ** 20,
     ("cfg5_128x4096x4096", (64, 128, 1, 8)): (80.07 + 16.00 + 16.03 + 2.00) * 2 ** 20,
     ("cfg5_4096x64x9216", (128, 64, 0, 8)): (161.99 + 8.00 + 8.03 + 1.00) * 2 ** 20,
+    # the convolution workloads, keyed by the whole configuration: profiles/conv2d_tuned_conv_*.txt
+    ("conv_3x3", (64, 8, 4, 1, 0, 1, 0, 1)): (144.02 + 128.00) * 2 ** 20,
+    ("conv_7x7", (32, 8, 8, 2, 0, 8, 0, 1)): (144.45 + 128.00) * 2 ** 20,
+    ("conv_11x11", (32, 8, 4, 8, 0, 4, 0, 1)): (170.42 + 128.00) * 2 ** 20,
 }
 
 
@@ -88,6 +95,109 @@ def cpu_blocked_baseline(w, A, B, C):
             "sample": f"the whole workload once, {t:.2f} s"}
 
 
+PEAK_HBM_TBS = 8.0                 # MI355X published HBM3E bandwidth
+PEAK_FP32_PLAIN_TFLOPS = 78.6      # 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz: one v_fma_f32
+                                   # per lane and cycle; the published 157.3 needs packed FP32
+
+
+def conv_main(a):
+    """The second kernel family: one step = one conv2d_tuned() call on the resident image of a
+    convolution workload (paper's first case study).  Figures of merit as the paper counts them:
+    GFLOP/s = (1 + 2 Xf Yf) X Y / t, GB/s = 2 X Y floats / t."""
+    import numpy as np
+    import torch
+    from paper_1703_06503_amd import binding as b
+    from paper_1703_06503_amd import synth
+    from oracle import conv_oracle as co
+
+    w = synth.CONV_WORKLOADS[a.workload]
+    A, F = synth.make_conv_workload(w)
+    torch.cuda.set_device(0)
+    dA, dF = torch.from_numpy(A).cuda(), torch.from_numpy(F).cuda()
+    dB = torch.empty((w.Y, w.X), dtype=torch.float32, device="cuda")
+    lda = A.shape[1]
+    tuning = {"budget": a.tune_budget}
+    if a.tune_budget > 0:
+        o = b.tune_opts()
+        o.sa_T = 4.0
+        t0 = time.perf_counter()
+        evals, res = b.conv2d_tune(w.X, w.Y, w.Xf, w.Yf, w.w, b.STRATEGY_ANNEALING, a.tune_budget, w.seed, o)
+        tuning.update({"strategy": "annealing T=4", "space_size": res.space_size, "evaluations": evals,
+                       "failed": res.failed, "seconds": time.perf_counter() - t0,
+                       "found_config": list(res.best.as_tuple()), "found_ms": res.best_ms})
+    exact, used = b.conv2d_config_select(w.X, w.Y, w.Xf, w.Yf)
+
+    def step():
+        b.conv2d_tuned(w.X, w.Y, w.Xf, w.Yf, w.w, dF, dA, lda, dB, w.X)
+
+    for _ in range(a.warmup):
+        step()
+    # a launch lasts some tens of microseconds and the clock needs about 25 ms of load to settle:
+    # keep launching, untimed, until that much time has passed
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < 0.03:
+        for _ in range(50):
+            step()
+        torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(a.steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / a.steps
+    kernel_ms = ev0.elapsed_time(ev1) / a.steps
+
+    rng = np.random.default_rng(w.seed)
+    ys = np.concatenate([[0, w.Y - 1], rng.integers(0, w.Y, 1024)])
+    xs = np.concatenate([[0, w.X - 1], rng.integers(0, w.X, 1024)])
+    ref = co.conv2d_sample(A, F, w.w, ys, xs)
+    got = dB.cpu().numpy()[ys, xs].astype(np.float64)
+    ratio = float(np.max(np.abs(got - ref) / co.tolerance(ref, F, A, w.w)))
+    if not ratio <= 1.0:
+        print(f"bench.py: result outside the parity bound (err/bound = {ratio})", file=sys.stderr)
+        return 1
+
+    flops = (1.0 + 2.0 * w.Xf * w.Yf) * w.X * w.Y
+    # algorithmic bytes: the stored image with its halo read once, the output written once
+    abytes = 4.0 * ((w.X + w.Xf - 1) * (w.Y + w.Yf - 1) + w.X * w.Y)
+    tflops = flops / (kernel_ms * 1e-3) * 1e-12
+    tbs = abytes / (kernel_ms * 1e-3) * 1e-12
+    hbm_bound = abytes / PEAK_HBM_TBS > flops / PEAK_FP32_PLAIN_TFLOPS
+    roof = ({"bound": "hbm", "achieved": tbs * 1e3, "peak": PEAK_HBM_TBS * 1e3, "unit": "GB/s",
+             "frac": tbs / PEAK_HBM_TBS} if hbm_bound else
+            {"bound": "alu", "achieved": tflops, "peak": PEAK_FP32_TFLOPS, "unit": "TFLOP/s",
+             "frac": tflops / PEAK_FP32_TFLOPS,
+             "peak_without_packed_fp32": PEAK_FP32_PLAIN_TFLOPS,
+             "frac_without_packed_fp32": tflops / PEAK_FP32_PLAIN_TFLOPS})
+    roof.update({"traffic": MEASURED_TRAFFIC_BYTES.get((a.workload, tuple(used.as_tuple()))),
+                 "traffic_unit": "bytes per launch", "kernel_ms": kernel_ms,
+                 "flops_per_launch": flops, "algorithmic_bytes": abytes})
+    out = {
+        "metric": f"best-tuned 2D convolution GFLOP/s ({a.workload})",
+        "value": flops / (ms_per_step * 1e-3) * 1e-9, "unit": "GFLOP/s", "n_gpus": 1,
+        "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{a.workload}: {w.Xf}x{w.Yf} filter on a {w.X}x{w.Y} image "
+                               f"(stored with its halo, rows of {lda} floats), w={w.w:.6g}, uniform seed {w.seed}",
+                   "kernel_config": dict(zip(b.CONV_FIELDS, used.as_tuple())),
+                   "from": "this run's search or conv2d_config_set" if exact else "built-in default"},
+        "gb_per_s_as_the_paper_counts": 2.0 * w.X * w.Y * 4 / (kernel_ms * 1e-3) * 1e-9,
+        "parity_err_over_bound": ratio, "tuning": tuning, "roofline": roof,
+    }
+    if not a.no_cpu_baseline:
+        # the oracle as it stands (numpy float64, one shifted slice per tap) on the whole image
+        t0 = time.perf_counter()
+        co.conv2d(A, F, w.w, w.X, w.Y)
+        sec = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": flops / sec * 1e-9, "unit": "GFLOP/s", "cores": 1, "kind": "oracle",
+                               "sample": f"the whole {w.X}x{w.Y} image, {sec:.1f} s"}
+    print(json.dumps(out))
+    return 0
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -106,6 +216,9 @@ def main():
         print("bench.py: this build runs on exactly one GPU (--gpus 1); sharding across several "
               "GPUs is a design note only and is not implemented", file=sys.stderr)
         return 2
+
+    if a.workload.startswith("conv_"):
+        return conv_main(a)
 
     import numpy as np
     import torch

@@ -47,7 +47,8 @@ uint64_t fnv1a(const void *data, size_t n, uint64_t h = 1469598103934665603ull) 
 }
 
 std::string default_cache_dir() {
-    if (const char *env = std::getenv("SGEMM_TUNED_CACHE_DIR")) return env;
+    if (const char *env = std::getenv("SGEMM_TUNED_CACHE_DIR"))
+        if (*env) return env; // an empty value counts as unset
     Dl_info info;
     if (dladdr((const void *)&default_cache_dir, &info) && info.dli_fname) {
         std::string p = info.dli_fname;

@@ -17,6 +17,19 @@ import sys
 import numpy as np
 
 SPACES = {"full": 0, "small": 1, "mfma": 2}
+CONV_SPACES = {"conv3x3": (3, 3), "conv7x7": (7, 7), "conv11x11": (11, 11)}  # second kernel family
+
+
+def space_size_and_replay(name):
+    """(number of configurations, replay(table, strategy, budget, seed, opts)) of a named space."""
+    from . import binding as b
+    if name in CONV_SPACES:
+        Xf, Yf = CONV_SPACES[name]
+        return (b.conv2d_space_size(Xf, Yf),
+                lambda t, strategy, budget, seed, opts: b.conv2d_tune_replay(Xf, Yf, t, strategy, budget, seed, opts))
+    space = SPACES[name]
+    return (b.sgemm_space_size(space),
+            lambda t, strategy, budget, seed, opts: b.tune_replay(space, t, strategy, budget, seed, opts))
 
 
 def convert_log(jsonl_path, csv_path):
@@ -43,7 +56,10 @@ def load_table(csv_path, n):
 
 
 def study(table, space, budget, runs):
+    """space: a preset number of the GEMM family, or a replay function of space_size_and_replay()."""
     from . import binding as b
+    replay = space if callable(space) else (
+        lambda t, strategy, budget, seed, opts: b.tune_replay(space, t, strategy, budget, seed, opts))
     ok = table[table > 0]
     opt = float(ok.min())
     settings = [("random", b.STRATEGY_RANDOM, {})]
@@ -59,7 +75,7 @@ def study(table, space, budget, runs):
             setattr(opts, k, v)
         rel, to5 = [], []
         for seed in range(runs):
-            ev, res, visited = b.tune_replay(space, table, strategy, budget, seed, opts)
+            ev, res, visited = replay(table, strategy, budget, seed, opts)
             rel.append(opt / res.best_ms)          # fraction of the optimum's speed reached
             # evaluations spent until a configuration within 5 % of the optimum was timed
             hit = next((i + 1 for i, v in enumerate(visited) if 0 < table[v] <= 1.05 * opt), None)
@@ -80,15 +96,13 @@ def main(argv=None):
     ap = argparse.ArgumentParser()
     ap.add_argument("table")
     ap.add_argument("--from-log", default=None, help="JSONL log to convert into TABLE first")
-    ap.add_argument("--space", choices=sorted(SPACES), default="full")
+    ap.add_argument("--space", choices=sorted(SPACES) + sorted(CONV_SPACES), default="full")
     ap.add_argument("--budget", type=int, nargs="+", default=[500])
     ap.add_argument("--runs", type=int, default=128)
     a = ap.parse_args(argv)
     if a.from_log:
         print(f"converted {convert_log(a.from_log, a.table)} evaluations", file=sys.stderr)
-    from . import binding as b
-    space = SPACES[a.space]
-    n = b.sgemm_space_size(space)
+    n, space = space_size_and_replay(a.space)
     table = load_table(a.table, n)
     ok = table[table > 0]
     print(f"space {a.space}: {n} configurations, {len(ok)} with a time, optimum {ok.min():.4f} ms; "

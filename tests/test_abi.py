@@ -1,5 +1,5 @@
-"""The C-ABI library loads without a GPU and exports every symbol include/sgemm_tuned.h
-declares; host-only entry points answer; argument checks reject bad input before any launch."""
+"""The C-ABI library loads without a GPU and exports every symbol the headers under include/
+declare; host-only entry points answer; argument checks reject bad input before any launch."""
 import ctypes
 import os
 import re
@@ -12,9 +12,12 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "sgemm_tuned.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b([a-z_0-9]+)\s*\(", text)) - {"defined"})
+    names = set()
+    for header in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b([a-z_0-9]+)\s*\(", text))
+    return sorted(names - {"defined"})
 
 
 def test_every_declared_symbol_is_exported_and_bound():
@@ -39,6 +42,8 @@ def test_struct_sizes_match_the_header():
     assert ctypes.sizeof(b.sgemm_config) == 16 * 4
     assert ctypes.sizeof(b.sgemm_kernel_info) == 8 * 4
     assert ctypes.sizeof(b.tune_result) == 16 * 4 + 9 * 4 + 6 * 4
+    assert ctypes.sizeof(b.conv2d_config) == 8 * 4
+    assert ctypes.sizeof(b.conv2d_tune_result) == 8 * 4 + 10 * 4 + 4 * 4
 
 
 def test_bad_arguments_are_rejected_without_a_gpu():
