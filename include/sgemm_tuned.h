@@ -260,6 +260,14 @@ int sgemm_kernel_cache_dir(const char *path);
  * bounds-guarded form.  cfg->sk > 1 selects the build that split-K launches use (one build
  * for every sk > 1: the split itself is a launch parameter).  Needs no GPU.  info may be null. */
 int sgemm_kernel_compile(const sgemm_config *cfg, int layout, int edge, sgemm_kernel_info *info);
+/* [host] Which build a call with cfg launches for these sizes and leading dimensions when the
+ * operands' pointers are 16-byte aligned: *variant receives the configuration as it is built
+ * (vector widths narrowed where a stored row is not a multiple of them, fewer LDS buffers or
+ * register staging where narrowed LDS-direct loads no longer fit, sk = 1 when K is not split)
+ * and *edge whether it is the guarded build, so that sgemm_kernel_compile(variant, layout,
+ * *edge) prepares exactly what the call will load. */
+int sgemm_kernel_resolve(const sgemm_config *cfg, int M, int N, int K, int lda, int ldb, int ldc,
+                         int layout, sgemm_config *variant, int *edge);
 /* [host] Path of the variant's code object in the cache directory (whether or not it exists
  * yet), NUL-terminated into buf: lets a deployment ship exactly the variants it uses. */
 int sgemm_kernel_cache_path(const sgemm_config *cfg, int layout, int edge, char *buf, int cap);

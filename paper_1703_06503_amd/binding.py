@@ -122,7 +122,7 @@ EXPORTS = (
     "sgemm_space_get", "sgemm_space_find", "sgemm_space_dims", "sgemm_space_values",
     "sgemm_config_check", "sgemm_config_lds_bytes", "sgemm_config_default",
     "sgemm_config_workspace_bytes",
-    "sgemm_kernel_cache_dir", "sgemm_kernel_compile", "sgemm_kernel_macros",
+    "sgemm_kernel_cache_dir", "sgemm_kernel_compile", "sgemm_kernel_resolve", "sgemm_kernel_macros",
     "sgemm_kernel_cache_path", "sgemm_config_get",
     "sgemm_config_set", "sgemm_config_select", "sgemm_cache_load", "sgemm_cache_save",
     "sgemm_cache_clear", "sgemm_cache_count", "sgemm_device_peak", "sgemm_status_string",
@@ -183,6 +183,7 @@ def lib():
         L.sgemm_kernel_cache_dir.argtypes = [ctypes.c_char_p]
         L.sgemm_kernel_compile.argtypes = [cfgp, i, i, ctypes.POINTER(sgemm_kernel_info)]
         L.sgemm_kernel_macros.argtypes = [cfgp, i, i, ctypes.c_char_p, i]
+        L.sgemm_kernel_resolve.argtypes = [cfgp, i, i, i, i, i, i, i, cfgp, ctypes.POINTER(i)]
         L.sgemm_config_get.argtypes = [i, i, i, i, cfgp]
         L.sgemm_config_set.argtypes = [i, i, i, i, cfgp, f]
         L.sgemm_config_select.argtypes = [i, i, i, i, cfgp]
@@ -390,6 +391,14 @@ def sgemm_kernel_cache_path(cfg, layout=0, edge=0):
     _check(lib().sgemm_kernel_cache_path(ctypes.byref(cfg), layout, edge, buf, 4096),
            "sgemm_kernel_cache_path")
     return os.fsdecode(buf.value)
+
+
+def sgemm_kernel_resolve(cfg, M, N, K, lda, ldb, ldc, layout=0):
+    """Returns (configuration as built, edge)."""
+    out, edge = sgemm_config(), ctypes.c_int(0)
+    _check(lib().sgemm_kernel_resolve(ctypes.byref(cfg), M, N, K, lda, ldb, ldc, layout,
+                                      ctypes.byref(out), ctypes.byref(edge)), "sgemm_kernel_resolve")
+    return out, edge.value
 
 
 def sgemm_kernel_macros(cfg, layout=0, edge=0):

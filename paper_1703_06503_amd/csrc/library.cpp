@@ -806,6 +806,18 @@ int sgemm_kernel_compile(const sgemm_config *cfg, int layout, int edge, sgemm_ke
     return rc;
 }
 
+int sgemm_kernel_resolve(const sgemm_config *cfg, int M, int N, int K, int lda, int ldb, int ldc,
+                         int layout, sgemm_config *variant, int *edge) {
+    if (!cfg || !variant || !edge || M <= 0 || N <= 0 || K <= 0 || layout < 0 || layout > 3) return SGEMM_E_BADARG;
+    if (violates(*cfg)) return SGEMM_E_INVALID;
+    const float *aligned = reinterpret_cast<const float *>(uintptr_t{256}); // stands for any aligned pointer
+    const VariantKey key = resolve_variant(*cfg, M, N, K, aligned, lda, aligned, ldb, aligned, ldc, layout);
+    *variant = key.cfg;
+    variant->sk = key.splitk ? std::max(2, cfg->sk) : 1;
+    *edge = key.edge;
+    return SGEMM_OK;
+}
+
 int sgemm_kernel_cache_path(const sgemm_config *cfg, int layout, int edge, char *buf, int cap) {
     if (!cfg || !buf || cap <= 0 || layout < 0 || layout > 3) return SGEMM_E_BADARG;
     if (violates(*cfg)) return SGEMM_E_INVALID;

@@ -10,8 +10,6 @@ import sys
 sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
 
 from paper_1703_06503_amd import binding as b            # noqa: E402
-from paper_1703_06503_amd.precompile import precompile   # noqa: E402
-from tests import gpu_util as gu                         # noqa: E402
 from tests import test_gpu_parity as t                   # noqa: E402
 
 
@@ -51,26 +49,30 @@ def conv_variants():
                 b.conv2d_kernel_compile(cfg, Xf, Yf, edge, vector)
 
 
+def _resolve_and_compile(task):
+    space, index, (M, N, K), layout = task
+    cfg = b.sgemm_space_get(space, index)
+    lda = M if layout & 1 else K
+    ldb = K if layout & 2 else N
+    variant, edge = b.sgemm_kernel_resolve(cfg, M, N, K, lda, ldb, N, layout)
+    return 0 if b.sgemm_kernel_compile(variant, layout, edge).from_cache else 1
+
+
+def sweep_variants(jobs):
+    """Exactly the build each case of the parity sweeps loads: which one that is depends on the
+    sizes too (vector widths are narrowed where a stored row is not a multiple of them)."""
+    import multiprocessing as mp
+    tasks = [(space, i, shape, layout) for space, idx, shape, layout in t.all_sweeps() for i in idx]
+    with mp.get_context("spawn").Pool(jobs) as pool:
+        new = sum(pool.map(_resolve_and_compile, tasks, chunksize=8))
+    print(f"parity sweeps: {len(tasks)} cases, {new} variants compiled now", flush=True)
+
+
 def main():
     jobs = min(8, os.cpu_count() or 1)
     tuned_table_variants()
     fixed_config_variants()
     conv_variants()
-    precompile(b.SPACE_SMALL, (0,), (0,), jobs)
-    full = gu.sample_configs(**t.FULL_SAMPLE)
-    precompile(b.SPACE_FULL, (0,), (0, 1), jobs, indices=full)
-    mfma = gu.sample_configs(**t.MFMA_SAMPLE)
-    precompile(b.SPACE_MFMA, (0,), (0, 1), jobs, indices=mfma)
-    precompile(b.SPACE_EXT, (0,), (0, 1), jobs, indices=gu.sample_configs(**t.EXT_SAMPLE))
-    precompile(b.SPACE_DIRECT, (0,), (0, 1), jobs, indices=gu.sample_configs(**t.DIRECT_SAMPLE))
-    for layout in (1, 2, 3):
-        precompile(b.SPACE_FULL, (layout,), (0, 1), jobs,
-                   indices=gu.sample_configs(b.SPACE_FULL, 40, seed=100 + layout))
-        precompile(b.SPACE_EXT, (layout,), (1,), jobs,
-                   indices=gu.sample_configs(b.SPACE_EXT, 24, seed=200 + layout))
-        precompile(b.SPACE_DIRECT, (layout,), (0, 1), jobs,
-                   indices=gu.sample_configs(b.SPACE_DIRECT, 24, seed=300 + layout))
-
-
+    sweep_variants(jobs)
 if __name__ == "__main__":
     main()

@@ -23,6 +23,26 @@ RAGGED_SHAPE = (200, 136, 68)     # guarded variants, several tiles for small co
 RAGGED_BIG = (300, 520, 44)       # more than one tile even at 256 x 256
 
 
+def all_sweeps():
+    """(space, configuration indices, shape, layout) of every sweep below: what
+    tests/precompile_test_variants.py puts into the kernel cache."""
+    full, mfma = gu.sample_configs(**FULL_SAMPLE), gu.sample_configs(**MFMA_SAMPLE)
+    ext, direct = gu.sample_configs(**EXT_SAMPLE), gu.sample_configs(**DIRECT_SAMPLE)
+    out = [(b.SPACE_SMALL, list(range(16)), (256, 256, 256), 0),
+           (b.SPACE_FULL, full, EXACT_SHAPE, 0), (b.SPACE_FULL, full, RAGGED_SHAPE, 0),
+           (b.SPACE_MFMA, mfma, EXACT_SHAPE, 0), (b.SPACE_MFMA, mfma, RAGGED_BIG, 0),
+           (b.SPACE_EXT, ext, EXACT_EXT, 0), (b.SPACE_EXT, ext, RAGGED_EXT, 0),
+           (b.SPACE_DIRECT, direct, EXACT_EXT, 0), (b.SPACE_DIRECT, direct, RAGGED_EXT, 0),
+           (b.SPACE_DIRECT, direct[::4], (203, 137, 67), 0)]
+    for layout in (1, 2, 3):
+        d = gu.sample_configs(b.SPACE_DIRECT, 24, seed=300 + layout)
+        out += [(b.SPACE_DIRECT, d, EXACT_EXT, layout), (b.SPACE_DIRECT, d, RAGGED_EXT, layout),
+                (b.SPACE_EXT, gu.sample_configs(b.SPACE_EXT, 24, seed=200 + layout), RAGGED_EXT, layout)]
+        f = gu.sample_configs(b.SPACE_FULL, 40, seed=100 + layout)
+        out += [(b.SPACE_FULL, f, EXACT_SHAPE, layout), (b.SPACE_FULL, f, RAGGED_SHAPE, layout)]
+    return out
+
+
 def _sweep(space, indices, shape, alpha, beta, layout, seed, dist="uniform"):
     M, N, K = shape
     A, B, C = synth.make_inputs(M, N, K, layout, seed, dist)
