@@ -115,6 +115,17 @@ class conv2d_tune_result(ctypes.Structure):
                 ("compile_ms", ctypes.c_float), ("reserved", ctypes.c_int * 4)]
 
 
+class ktuner_result(ctypes.Structure):
+    _fields_ = [("best_index", ctypes.c_int), ("best_ms", ctypes.c_float),
+                ("evaluations", ctypes.c_int), ("failed", ctypes.c_int),
+                ("space_size", ctypes.c_int), ("evals_to_best", ctypes.c_int),
+                ("failed_verify", ctypes.c_int), ("total_ms", ctypes.c_float),
+                ("compile_ms", ctypes.c_float), ("reserved", ctypes.c_int * 7)]
+
+
+KTUNER_CONSTRAINT = ctypes.CFUNCTYPE(ctypes.c_int, ctypes.POINTER(ctypes.c_int), ctypes.c_void_p)
+
+
 EXPORTS = (
     "sgemm_tuned", "sgemm_tuned_on", "sgemm_tuned_online", "sgemm_set_stream", "sgemm_run_config",
     "sgemm_run_config_padded", "sgemm_reference",
@@ -132,6 +143,13 @@ EXPORTS = (
     "conv2d_config_lds_bytes", "conv2d_config_threads", "conv2d_kernel_compile",
     "conv2d_run_config", "conv2d_reference", "conv2d_tuned", "conv2d_config_set",
     "conv2d_config_select", "conv2d_tune", "conv2d_tune_replay",
+    # include/kernel_tuner.h
+    "ktuner_create", "ktuner_destroy", "ktuner_add_parameter", "ktuner_mul_global_size",
+    "ktuner_div_global_size", "ktuner_mul_local_size", "ktuner_div_local_size",
+    "ktuner_add_constraint", "ktuner_add_argument_input", "ktuner_add_argument_output",
+    "ktuner_add_argument_int", "ktuner_add_argument_float", "ktuner_set_reference",
+    "ktuner_set_tolerance", "ktuner_space_size", "ktuner_space_get", "ktuner_compile",
+    "ktuner_launch_shape", "ktuner_tune", "ktuner_time_of", "ktuner_read_output",
 )
 
 _lib = None
@@ -215,6 +233,32 @@ def lib():
         L.conv2d_tune_replay.argtypes = [i, i, ctypes.POINTER(f), i, i, i, ctypes.c_ulonglong,
                                          ctypes.POINTER(tune_opts), ctypes.POINTER(i), i,
                                          ctypes.POINTER(conv2d_tune_result)]
+        i3 = ctypes.POINTER(ctypes.c_int)
+        names3 = ctypes.POINTER(ctypes.c_char_p)
+        L.ktuner_create.argtypes = [ctypes.c_char_p, ctypes.c_char_p, i3, i3]
+        L.ktuner_create.restype = vp
+        L.ktuner_destroy.argtypes = [vp]
+        L.ktuner_destroy.restype = None
+        L.ktuner_add_parameter.argtypes = [vp, ctypes.c_char_p, i3, i]
+        for fn in (L.ktuner_mul_global_size, L.ktuner_div_global_size, L.ktuner_mul_local_size,
+                   L.ktuner_div_local_size):
+            fn.argtypes = [vp, names3]
+        L.ktuner_add_constraint.argtypes = [vp, KTUNER_CONSTRAINT, names3, i, vp]
+        L.ktuner_add_argument_input.argtypes = [vp, vp, ctypes.c_size_t]
+        L.ktuner_add_argument_output.argtypes = [vp, vp, ctypes.c_size_t]
+        L.ktuner_add_argument_int.argtypes = [vp, i]
+        L.ktuner_add_argument_float.argtypes = [vp, f]
+        L.ktuner_set_reference.argtypes = [vp, ctypes.c_char_p, ctypes.c_char_p, i3, i3]
+        L.ktuner_set_tolerance.argtypes = [vp, f, f]
+        L.ktuner_space_size.argtypes = [vp]
+        L.ktuner_space_get.argtypes = [vp, i, i3]
+        L.ktuner_compile.argtypes = [vp, i, ctypes.POINTER(sgemm_kernel_info)]
+        L.ktuner_launch_shape.argtypes = [vp, i, i3, i3]
+        L.ktuner_tune.argtypes = [vp, i, i, ctypes.c_ulonglong, ctypes.POINTER(tune_opts),
+                                  ctypes.POINTER(ktuner_result)]
+        L.ktuner_time_of.argtypes = [vp, i]
+        L.ktuner_time_of.restype = f
+        L.ktuner_read_output.argtypes = [vp, i, vp, ctypes.c_size_t]
         _lib = L
     return _lib
 
@@ -531,3 +575,123 @@ def conv2d_tune_replay(Xf, Yf, ms_table, strategy, budget, seed=0, opts=None):
                                          ctypes.byref(opts) if opts is not None else None,
                                          visited, n, ctypes.byref(res)), "conv2d_tune_replay")
     return ev, res, list(visited[:ev])
+
+
+# ---- include/kernel_tuner.h -----------------------------------------------------------------
+def _int3(v):
+    return (ctypes.c_int * 3)(*v)
+
+
+def _names3(names):
+    return (ctypes.c_char_p * 3)(*[n.encode() if n else None for n in names])
+
+
+def ktuner_create(source, entry, global_size, local_size):
+    h = lib().ktuner_create(source.encode(), entry.encode(), _int3(global_size), _int3(local_size))
+    if not h:
+        raise SgemmError(E_BADARG, "ktuner_create")
+    return h
+
+
+def ktuner_destroy(t):
+    lib().ktuner_destroy(t)
+
+
+def ktuner_add_parameter(t, name, values):
+    arr = (ctypes.c_int * len(values))(*values)
+    return _check(lib().ktuner_add_parameter(t, name.encode(), arr, len(values)), "ktuner_add_parameter")
+
+
+def ktuner_mul_global_size(t, names):
+    return _check(lib().ktuner_mul_global_size(t, _names3(names)), "ktuner_mul_global_size")
+
+
+def ktuner_div_global_size(t, names):
+    return _check(lib().ktuner_div_global_size(t, _names3(names)), "ktuner_div_global_size")
+
+
+def ktuner_mul_local_size(t, names):
+    return _check(lib().ktuner_mul_local_size(t, _names3(names)), "ktuner_mul_local_size")
+
+
+def ktuner_div_local_size(t, names):
+    return _check(lib().ktuner_div_local_size(t, _names3(names)), "ktuner_div_local_size")
+
+
+_ktuner_callbacks = {}   # handle -> ctypes callbacks that must outlive the tuner
+
+
+def ktuner_add_constraint(t, fn, names):
+    """fn(list of values) -> bool, for the named parameters in that order."""
+    n = len(names)
+    cb = KTUNER_CONSTRAINT(lambda values, _user: 1 if fn([values[k] for k in range(n)]) else 0)
+    _ktuner_callbacks.setdefault(t, []).append(cb)
+    arr = (ctypes.c_char_p * n)(*[x.encode() for x in names])
+    return _check(lib().ktuner_add_constraint(t, cb, arr, n, None), "ktuner_add_constraint")
+
+
+def ktuner_add_argument_input(t, array):
+    """array: a contiguous numpy array (host)."""
+    return _check(lib().ktuner_add_argument_input(t, array.ctypes.data, array.nbytes),
+                  "ktuner_add_argument_input")
+
+
+def ktuner_add_argument_output(t, array):
+    return _check(lib().ktuner_add_argument_output(t, array.ctypes.data, array.nbytes),
+                  "ktuner_add_argument_output")
+
+
+def ktuner_add_argument_int(t, value):
+    return _check(lib().ktuner_add_argument_int(t, value), "ktuner_add_argument_int")
+
+
+def ktuner_add_argument_float(t, value):
+    return _check(lib().ktuner_add_argument_float(t, value), "ktuner_add_argument_float")
+
+
+def ktuner_set_reference(t, source, entry, global_size, local_size):
+    return _check(lib().ktuner_set_reference(t, source.encode(), entry.encode(), _int3(global_size),
+                                             _int3(local_size)), "ktuner_set_reference")
+
+
+def ktuner_set_tolerance(t, abs_tol, rel_tol):
+    return _check(lib().ktuner_set_tolerance(t, abs_tol, rel_tol), "ktuner_set_tolerance")
+
+
+def ktuner_space_size(t):
+    return _check(lib().ktuner_space_size(t), "ktuner_space_size")
+
+
+def ktuner_space_get(t, index, n_params):
+    v = (ctypes.c_int * n_params)()
+    _check(lib().ktuner_space_get(t, index, v), "ktuner_space_get")
+    return tuple(v)
+
+
+def ktuner_compile(t, index):
+    info = sgemm_kernel_info()
+    _check(lib().ktuner_compile(t, index, ctypes.byref(info)), "ktuner_compile")
+    return info
+
+
+def ktuner_launch_shape(t, index):
+    g, l = (ctypes.c_int * 3)(), (ctypes.c_int * 3)()
+    _check(lib().ktuner_launch_shape(t, index, g, l), "ktuner_launch_shape")
+    return tuple(g), tuple(l)
+
+
+def ktuner_tune(t, strategy, budget=0, seed=0, opts=None):
+    """Returns (evaluations, ktuner_result)."""
+    res = ktuner_result()
+    n = _check(lib().ktuner_tune(t, strategy, budget, seed,
+                                 ctypes.byref(opts) if opts is not None else None,
+                                 ctypes.byref(res)), "ktuner_tune")
+    return n, res
+
+
+def ktuner_time_of(t, index):
+    return lib().ktuner_time_of(t, index)
+
+
+def ktuner_read_output(t, which, array):
+    return _check(lib().ktuner_read_output(t, which, array.ctypes.data, array.nbytes), "ktuner_read_output")

@@ -9,7 +9,7 @@ LIBDIR = os.path.join(HERE, "lib")
 OBJDIR = os.path.join(LIBDIR, "obj")
 LIB = os.path.join(LIBDIR, "libsgemm_tuned.so")
 HIP_SOURCES = ["util_kernels.hip"]
-CPP_SOURCES = ["library.cpp", "space.cpp", "strategy.cpp", "kernelgen.cpp", "conv.cpp"]
+CPP_SOURCES = ["library.cpp", "space.cpp", "strategy.cpp", "kernelgen.cpp", "conv.cpp", "ktuner.cpp"]
 ROCM = os.environ.get("ROCM_PATH", "/opt/rocm")
 HIPCC = os.path.join(ROCM, "bin", "hipcc")
 # packed-FP32 instructions are kept out of all device code

@@ -191,10 +191,13 @@ std::string normalize(const char *p, const char *end) {
     return out;
 }
 
-const std::string &normalized_source(const KernelSource &src) {
+// The two built-in families are normalised once; a caller-supplied source each time it is used.
+std::string normalized_source(const KernelSource &src) {
     static const std::string gemm = normalize(sgemm_kernel_source_begin, sgemm_kernel_source_end);
     static const std::string conv = normalize(conv_kernel_source_begin, conv_kernel_source_end);
-    return src.begin == sgemm_kernel_source_begin ? gemm : conv;
+    if (src.begin == sgemm_kernel_source_begin) return gemm;
+    if (src.begin == conv_kernel_source_begin) return conv;
+    return normalize(src.begin, src.end) + "\n" + src.entry;
 }
 
 const KernelSource &gemm_source() {
@@ -214,7 +217,7 @@ const KernelSource &conv_source() {
 std::string code_object_path(const VariantKey &key) { return code_object_path(gemm_source(), key.macros()); }
 
 std::string code_object_path(const KernelSource &source, const std::string &macros) {
-    const std::string &src = normalized_source(source);
+    const std::string src = normalized_source(source);
     uint64_t h = fnv1a(src.data(), src.size());
     h = fnv1a(macros.data(), macros.size(), h);
     for (const char *f : kCompilerFlags) h = fnv1a(f, std::strlen(f), h);
