@@ -132,7 +132,10 @@ int get_loaded(const ConvVariant &v, std::shared_ptr<LoadedKernel> *out) {
     const int rc = load_kernel(conv_source(), macros, x_threads(v.cfg, v.Xf) * y_threads(v.cfg, v.Yf), &k, &log);
     if (rc != SGEMM_OK) { set_error(log); return rc; }
     std::lock_guard<std::mutex> lock(g_conv_mu);
-    if (g_loaded.size() >= kMaxLoaded) g_loaded.clear(); // running kernels keep their module alive
+    if (g_loaded.size() >= kMaxLoaded) {
+        (void)hipDeviceSynchronize(); // no variant may still be running when its module goes away
+        g_loaded.clear();
+    }
     g_loaded[macros] = k;
     *out = std::move(k);
     return SGEMM_OK;

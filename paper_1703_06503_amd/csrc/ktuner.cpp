@@ -473,6 +473,7 @@ int ktuner_tune(ktuner *t, int strategy, int budget, unsigned long long seed, co
             refresh();
             (void)hipModuleLaunchKernel(k->fn, grid[0], grid[1], grid[2], block[0], block[1], block[2], 0, s,
                                         argv.data(), nullptr);
+            (void)hipStreamSynchronize(s); // before k, and with it the module, goes away
         }
     }
     (void)hipStreamSynchronize(s);
