@@ -96,8 +96,10 @@ def cpu_blocked_baseline(w, A, B, C):
 
 
 PEAK_HBM_TBS = 8.0                 # MI355X published HBM3E bandwidth
-PEAK_FP32_PLAIN_TFLOPS = 78.6      # 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz: one v_fma_f32
-                                   # per lane and cycle; the published 157.3 needs packed FP32
+PEAK_FP32_PLAIN_TFLOPS = 78.6      # 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz: the rate of a
+                                   # v_fma_f32 that takes one source from a scalar register, as the
+                                   # convolution's FMAs take their filter coefficient (a loop of such
+                                   # FMAs measures 76 TFLOP/s, one with vector sources only 122)
 
 
 def conv_main(a):
@@ -179,8 +181,8 @@ def conv_measure(a, workload):
              "frac": tbs / PEAK_HBM_TBS} if hbm_bound else
             {"bound": "alu", "achieved": tflops, "peak": PEAK_FP32_TFLOPS, "unit": "TFLOP/s",
              "frac": tflops / PEAK_FP32_TFLOPS,
-             "peak_without_packed_fp32": PEAK_FP32_PLAIN_TFLOPS,
-             "frac_without_packed_fp32": tflops / PEAK_FP32_PLAIN_TFLOPS})
+             "peak_with_a_scalar_operand": PEAK_FP32_PLAIN_TFLOPS,
+             "frac_with_a_scalar_operand": tflops / PEAK_FP32_PLAIN_TFLOPS})
     roof.update({"traffic": MEASURED_TRAFFIC_BYTES.get((workload, tuple(used.as_tuple()))),
                  "traffic_unit": "bytes per launch", "kernel_ms": kernel_ms,
                  "flops_per_launch": flops, "algorithmic_bytes": abytes})
