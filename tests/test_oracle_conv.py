@@ -61,6 +61,26 @@ def test_linear_in_filter_and_image_and_only_the_used_part_of_a_wide_row_matters
         co.conv2d(A[:, :26], F, 1.0, 25, 14)                # halo missing
 
 
+def test_separable_filter_equals_a_row_pass_followed_by_a_column_pass():
+    """F = v u^T (outer product): the 2-D sum factors into a 1-D pass along x with u and a 1-D
+    pass along y with v.  Each pass is itself the oracle with a one-row or one-column filter, and
+    is checked against numpy's 1-D correlation on one line."""
+    X, Y, Xf, Yf = 37, 21, 5, 3
+    A, _ = synth.make_conv_inputs(X, Y, Xf, Yf, seed=7)
+    rng = np.random.default_rng(8)
+    u, v = rng.uniform(-1, 1, Xf), rng.uniform(-1, 1, Yf)
+    rows = co.conv2d(A, u[None, :], 1.0, X, Y + Yf - 1)            # along x, all stored rows
+    assert np.allclose(rows[4], np.correlate(A[4].astype(np.float64), u, mode="valid"), atol=1e-13)
+    both = co.conv2d(rows, v[:, None], 0.75, X, Y)                  # then along y
+    assert np.allclose(both, co.conv2d(A, np.outer(v, u), 0.75, X, Y), rtol=1e-12, atol=1e-12)
+
+
+def test_translation_of_the_image_translates_the_result():
+    A, F = synth.make_conv_inputs(30, 20, 3, 5, seed=9)
+    full = co.conv2d(A, F, 1.0, 30, 20)
+    assert np.array_equal(co.conv2d(A[3:, 4:], F, 1.0, 26, 17), full[3:, 4:])
+
+
 def test_sampled_values_equal_the_full_result():
     A, F = synth.make_conv_inputs(64, 48, 7, 7, seed=6)
     full = co.conv2d(A, F, 1.0 / 49, 64, 48)

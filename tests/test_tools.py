@@ -22,3 +22,23 @@ def test_report_reads_old_and_new_tables(tmp_path):
     # 2 * 4096^3 flop in 1 ms = 137 439 GFLOP/s = 87.4 % of 157.3 TFLOP/s
     assert "| 137439 | 87.4 |" in text
     assert text.count("\n") == 2 + 3
+
+
+def test_convolution_figures_of_merit_are_the_papers_counts():
+    """GFLOP/s = (1 + 2 Xf Yf) X Y / t and GB/s = 2 X Y floats / t (footnote of the section
+    "Best-found results" of the convolution case study)."""
+    from paper_1703_06503_amd import conv_cli, synth
+    w = synth.CONV_WORKLOADS["conv_7x7"]
+    gf, gb = conv_cli.figures(w, 1.0)                      # one millisecond
+    assert gf == (1 + 2 * 49) * 8192 * 4096 / 1e6 and gb == 2 * 8192 * 4096 * 4 / 1e6
+    assert synth.make_conv_inputs(8, 4, 3, 3, seed=1)[0].shape == (6, 10)
+
+
+def test_strategy_study_accepts_the_convolution_spaces():
+    import numpy as np
+    from paper_1703_06503_amd import strategy_study as ss
+    n, replay = ss.space_size_and_replay("conv7x7")
+    table = np.linspace(1.0, 2.0, n).astype(np.float32)     # configuration 0 is the optimum
+    opt, rows = ss.study(table, replay, 20, 4)
+    assert opt == 1.0 and len(rows) == 6
+    assert all(0 < r["mean_pct_of_best"] <= 100.0 for r in rows)
