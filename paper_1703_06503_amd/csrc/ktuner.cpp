@@ -133,7 +133,10 @@ int add_modifier(ktuner *t, bool global, bool multiply, const char *const names[
 
 int add_buffer(ktuner *t, Argument::Kind kind, const void *host, size_t bytes) {
     if (!t || !host || bytes == 0) return SGEMM_E_BADARG;
-    if (kind == Argument::Output && bytes % 4) { set_error("output arguments are float arrays"); return SGEMM_E_BADARG; }
+    if (kind == Argument::Output && (bytes % 4 || bytes / 4 > 0x7fffffffull)) {
+        set_error("output arguments are float arrays of fewer than 2^31 elements");
+        return SGEMM_E_BADARG;
+    }
     auto a = std::make_unique<Argument>();
     a->kind = kind;
     a->host.assign(static_cast<const char *>(host), static_cast<const char *>(host) + bytes);
