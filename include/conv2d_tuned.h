@@ -79,6 +79,14 @@ int conv2d_tuned(int X, int Y, int Xf, int Yf, float w, const float *F, const fl
 int conv2d_config_set(int X, int Y, int Xf, int Yf, const conv2d_config *cfg, float ms);
 int conv2d_config_select(int X, int Y, int Xf, int Yf, conv2d_config *out); /* 1 = exact, 0 = else */
 
+/* [host] The table of best configurations as a text file, one line per problem
+ * ("X Y Xf Yf ms XWG YWG XWPT YWPT LMEM VW PAD UNR"; '#' starts a comment).  save returns the
+ * number of entries written; load merges (a faster or first entry wins; lines this build cannot
+ * run are skipped) and returns the number of lines taken; clear empties the table. */
+int conv2d_cache_save(const char *path);
+int conv2d_cache_load(const char *path);
+int conv2d_cache_clear(void);
+
 /* ---- tuning ----------------------------------------------------------------------------
  * Searches the space of an Xf x Yf filter on an X x Y image with library-owned seeded operands
  * (image rows padded to a multiple of 16 floats, so that no vector width is ruled out by

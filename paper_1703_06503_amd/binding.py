@@ -142,7 +142,8 @@ EXPORTS = (
     "conv2d_space_size", "conv2d_space_get", "conv2d_space_find", "conv2d_config_check",
     "conv2d_config_lds_bytes", "conv2d_config_threads", "conv2d_kernel_compile",
     "conv2d_run_config", "conv2d_reference", "conv2d_tuned", "conv2d_config_set",
-    "conv2d_config_select", "conv2d_tune", "conv2d_tune_replay",
+    "conv2d_config_select", "conv2d_tune", "conv2d_tune_replay", "conv2d_cache_save",
+    "conv2d_cache_load", "conv2d_cache_clear",
     # include/kernel_tuner.h
     "ktuner_create", "ktuner_destroy", "ktuner_add_parameter", "ktuner_mul_global_size",
     "ktuner_div_global_size", "ktuner_mul_local_size", "ktuner_div_local_size",
@@ -228,6 +229,9 @@ def lib():
         L.conv2d_tuned.argtypes = conv
         L.conv2d_config_set.argtypes = [i, i, i, i, ccfgp, f]
         L.conv2d_config_select.argtypes = [i, i, i, i, ccfgp]
+        L.conv2d_cache_save.argtypes = [ctypes.c_char_p]
+        L.conv2d_cache_load.argtypes = [ctypes.c_char_p]
+        L.conv2d_cache_clear.argtypes = []
         L.conv2d_tune.argtypes = [i, i, i, i, f, i, i, ctypes.c_ulonglong,
                                   ctypes.POINTER(tune_opts), ctypes.POINTER(conv2d_tune_result)]
         L.conv2d_tune_replay.argtypes = [i, i, ctypes.POINTER(f), i, i, i, ctypes.c_ulonglong,
@@ -554,6 +558,18 @@ def conv2d_config_select(X, Y, Xf, Yf):
     c = conv2d_config()
     exact = _check(lib().conv2d_config_select(X, Y, Xf, Yf, ctypes.byref(c)), "conv2d_config_select")
     return exact, c
+
+
+def conv2d_cache_save(path):
+    return _check(lib().conv2d_cache_save(path.encode()), "conv2d_cache_save")
+
+
+def conv2d_cache_load(path):
+    return _check(lib().conv2d_cache_load(path.encode()), "conv2d_cache_load")
+
+
+def conv2d_cache_clear():
+    return _check(lib().conv2d_cache_clear(), "conv2d_cache_clear")
 
 
 def conv2d_tune(X, Y, Xf, Yf, w, strategy, budget, seed=0, opts=None):

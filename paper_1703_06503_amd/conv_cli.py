@@ -112,6 +112,7 @@ def main(argv=None):
     p.add_argument("--sa-T", type=float, default=0.0)
     p.add_argument("--pso-S", type=int, default=0)
     p.add_argument("--log", default=None)
+    p.add_argument("--save", default=None, help="merge the winner into this table of best configurations")
     p = sub.add_parser("run")
     p.add_argument("--workload", required=True)
     p.add_argument("--config", default=None)
@@ -133,7 +134,13 @@ def main(argv=None):
         o.reps, o.warmup_ms, o.sa_T, o.pso_S, o.random_fraction = a.reps, a.warmup_ms, a.sa_T, a.pso_S, a.fraction
         if a.log:
             o.log_path = a.log.encode()
+        if a.save:
+            import os
+            if os.path.exists(a.save):
+                b.conv2d_cache_load(a.save)
         n, res = b.conv2d_tune(w.X, w.Y, w.Xf, w.Yf, w.w, STRATEGIES[a.strategy], a.budget, a.seed, o)
+        if a.save:
+            b.conv2d_cache_save(a.save)
         print(f"{a.workload}: {n} of {res.space_size} configurations evaluated ({res.failed} failed) in "
               f"{res.total_ms / 1e3:.1f} s (compiling {res.compile_ms / 1e3:.1f} s); best "
               f"{','.join(map(str, res.best.as_tuple()))}: {res.best_ms:.4f} ms = {res.best_gflops:.0f} GFLOP/s, "

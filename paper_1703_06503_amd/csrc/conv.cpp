@@ -335,6 +335,52 @@ int conv2d_config_select(int X, int Y, int Xf, int Yf, conv2d_config *out) {
     return select_locked(X, Y, Xf, Yf, out);
 }
 
+int conv2d_cache_save(const char *path) {
+    if (!path) return SGEMM_E_BADARG;
+    FILE *f = std::fopen(path, "w");
+    if (!f) { set_error(std::string("cannot write ") + path); return SGEMM_E_IO; }
+    std::lock_guard<std::mutex> lock(g_conv_mu);
+    std::fprintf(f, "# X Y Xf Yf ms XWG YWG XWPT YWPT LMEM VW PAD UNR\n");
+    for (const auto &kv : g_tuned) {
+        const conv2d_config &c = kv.second.cfg;
+        std::fprintf(f, "%d %d %d %d %.6g %d %d %d %d %d %d %d %d\n", std::get<2>(kv.first), std::get<3>(kv.first),
+                     std::get<0>(kv.first), std::get<1>(kv.first), kv.second.ms, c.xwg, c.ywg, c.xwpt, c.ywpt,
+                     c.lmem, c.vw, c.pad, c.unr);
+    }
+    const int n = (int)g_tuned.size();
+    return std::fclose(f) == 0 ? n : SGEMM_E_IO;
+}
+
+int conv2d_cache_load(const char *path) {
+    if (!path) return SGEMM_E_BADARG;
+    FILE *f = std::fopen(path, "r");
+    if (!f) { set_error(std::string("cannot read ") + path); return SGEMM_E_IO; }
+    char line[512];
+    int n = 0;
+    std::lock_guard<std::mutex> lock(g_conv_mu);
+    while (std::fgets(line, sizeof line, f)) {
+        int X, Y, Xf, Yf;
+        float ms;
+        conv2d_config c;
+        if (line[0] == '#') continue;
+        if (std::sscanf(line, "%d %d %d %d %f %d %d %d %d %d %d %d %d", &X, &Y, &Xf, &Yf, &ms, &c.xwg, &c.ywg,
+                        &c.xwpt, &c.ywpt, &c.lmem, &c.vw, &c.pad, &c.unr) != 13)
+            continue;
+        if (X <= 0 || Y <= 0 || !filter_ok(Xf, Yf) || violates(c, Xf, Yf)) continue; // skip what this build cannot run
+        auto it = g_tuned.find({Xf, Yf, X, Y});
+        if (it == g_tuned.end() || !(it->second.ms > 0) || (ms > 0 && ms < it->second.ms)) g_tuned[{Xf, Yf, X, Y}] = TunedConv{c, ms};
+        ++n;
+    }
+    std::fclose(f);
+    return n;
+}
+
+int conv2d_cache_clear(void) {
+    std::lock_guard<std::mutex> lock(g_conv_mu);
+    g_tuned.clear();
+    return SGEMM_OK;
+}
+
 int conv2d_tune_replay(int Xf, int Yf, const float *ms_table, int table_len, int strategy, int budget,
                        unsigned long long seed, const tune_opts *opts, int *visited, int visited_cap,
                        conv2d_tune_result *out) {

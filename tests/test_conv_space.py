@@ -92,3 +92,33 @@ def test_variants_compile_without_a_gpu_and_report_their_resources(tmp_path):
             assert info.lds_bytes == cs.lds_bytes(cfg, f, f)
     with pytest.raises(b.SgemmError):
         b.conv2d_kernel_compile(b.make_conv_config(64, 64, 1, 1, 0, 1, 0, 1), 3, 3)
+
+
+def test_table_of_best_configurations_round_trips_and_selects_the_nearest(tmp_path):
+    b.conv2d_cache_clear()
+    a7 = b.make_conv_config(32, 8, 8, 2, 0, 8, 0, 1)
+    b7 = b.make_conv_config(16, 16, 4, 4, 2, 4, 1, 1)
+    b.conv2d_config_set(8192, 4096, 7, 7, a7, 0.06)
+    b.conv2d_config_set(512, 512, 7, 7, b7, 0.002)
+    assert b.conv2d_config_select(8192, 4096, 7, 7)[0] == 1
+    exact, near = b.conv2d_config_select(600, 400, 7, 7)             # nearest image, same filter
+    assert exact == 0 and near.as_tuple() == b7.as_tuple()
+    exact, other = b.conv2d_config_select(600, 400, 3, 3)            # unseen filter: built-in default
+    assert exact == 0 and other.lmem == 0 and b.conv2d_config_check(other, 3, 3) == b.OK
+    path = str(tmp_path / "conv.txt")
+    assert b.conv2d_cache_save(path) == 2
+    with open(path, "a") as f:
+        f.write("100 100 7 7 0.5 64 64 1 1 0 1 0 1\n")                # too many threads: skipped
+        f.write("8192 4096 7 7 0.5 8 8 1 1 0 1 0 1\n")                # slower than the entry held
+        f.write("not a line\n")
+    b.conv2d_cache_clear()
+    assert b.conv2d_config_select(8192, 4096, 7, 7)[0] == 0
+    assert b.conv2d_cache_load(path) == 3
+    exact, got = b.conv2d_config_select(8192, 4096, 7, 7)
+    assert exact == 1 and got.as_tuple() == a7.as_tuple()
+    assert b.conv2d_config_select(100, 100, 7, 7)[0] == 0
+    with pytest.raises(b.SgemmError):
+        b.conv2d_cache_load(str(tmp_path / "missing.txt"))
+    with pytest.raises(b.SgemmError):
+        b.conv2d_config_set(8, 8, 7, 7, b.make_conv_config(64, 64, 1, 1, 0, 1, 0, 1))
+    b.conv2d_cache_clear()
