@@ -459,21 +459,21 @@ int conv2d_tune(int X, int Y, int Xf, int Yf, float w, int strategy, int budget,
             compile_ms_total += info.compile_ms;
             if (info.scratch_bytes > 0) { status = "spill"; break; }
             if (info.lds_bytes > kLdsLimitBytes) { status = "lds"; break; }
-            auto run = [&]() { return launch(s, *k, v, X, Y, w, dF.f(), dA.f(), lda, dB.f(), ldb); };
-            (void)hipEventRecord(ev0.e, s);
-            if (run() != SGEMM_OK) { status = "launch"; break; }
-            (void)hipEventRecord(ev1.e, s);
-            if (verify) (void)sgemm_util::launch_compare(s, dB.f(), ldb, ref.f(), X, Y, X, abs_tol, rel_tol, dwords);
-            unsigned int bits[2] = {0, 0};
-            if (verify) (void)hipMemcpyAsync(bits, dwords, 8, hipMemcpyDeviceToHost, s);
-            if (hipStreamSynchronize(s) != hipSuccess) { status = "fault"; hip_failure = 1; break; }
-            if (verify && bits[0] != 0) { status = "verify"; break; }
-            float first = 0.0f;
-            (void)hipEventElapsedTime(&first, ev0.e, ev1.e);
-            bool was_cut = false;
-            ms = time_configuration(s, [&] { (void)run(); }, first, rules, best_ms, ev0, ev1, &samples, &was_cut);
-            if (ms < 0.0) { status = "fault"; hip_failure = 1; break; }
-            if (was_cut) { status = "ok-cut"; break; }
+            const Measured m = run_verify_time(
+                s, nullptr, [&] { return launch(s, *k, v, X, Y, w, dF.f(), dA.f(), lda, dB.f(), ldb) == SGEMM_OK; },
+                verify ? std::function<int()>([&] {
+                    unsigned int bits[2] = {0, 0};
+                    (void)sgemm_util::launch_compare(s, dB.f(), ldb, ref.f(), X, Y, X, abs_tol, rel_tol, dwords);
+                    (void)hipMemcpyAsync(bits, dwords, 8, hipMemcpyDeviceToHost, s);
+                    if (hipStreamSynchronize(s) != hipSuccess) return -1;
+                    return bits[0] != 0 ? 1 : 0;
+                }) : std::function<int()>(),
+                rules, best_ms, ev0, ev1);
+            status = m.status;
+            samples = m.samples;
+            if (m.device_failed) hip_failure = 1;
+            if (std::strcmp(m.status, "ok") != 0) { if (std::strcmp(m.status, "ok-cut") == 0) ms = m.ms; break; }
+            ms = m.ms;
             if (best_ms == 0.0 || ms < best_ms) best_ms = ms;
         } while (false);
         if (logf) {

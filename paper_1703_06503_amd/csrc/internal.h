@@ -53,5 +53,25 @@ double time_configuration(hipStream_t s, const std::function<void()> &launch, fl
                           const TimingRules &rules, double best_ms, Event &ev0, Event &ev1,
                           int *samples, bool *was_cut);
 
+// The part of an evaluation that is the same for every kernel family, once the variant is loaded:
+// give the kernel fresh arguments, run it once between two events, compare its outputs with the
+// reference's, and time it by the rules above.
+//   fresh_arguments  restores whatever the kernel overwrites (may be empty)
+//   launch           one launch on s; false when HIP refused it
+//   outputs_differ   enqueues the comparison(s), waits for the stream and returns 1 when an
+//                    output is outside its bound, 0 when all match, -1 when the device failed;
+//                    empty = no verification (the stream is still waited for)
+// status is "ok", "ok-cut" (timed, but dropped early as hopeless), "launch", "verify" or "fault";
+// after "fault" the device is not to be used further (device_failed).  ms < 0 unless timed.
+struct Measured {
+    double ms = -1.0;
+    const char *status = "ok";
+    int samples = 0;
+    bool device_failed = false;
+};
+Measured run_verify_time(hipStream_t s, const std::function<void()> &fresh_arguments,
+                         const std::function<bool()> &launch, const std::function<int()> &outputs_differ,
+                         const TimingRules &rules, double best_ms, Event &ev0, Event &ev1);
+
 } // namespace detail
 } // namespace sgemm

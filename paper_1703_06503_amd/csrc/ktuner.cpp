@@ -420,35 +420,33 @@ int ktuner_tune(ktuner *t, int strategy, int budget, unsigned long long seed, co
             info = k->info;
             compile_ms_total += info.compile_ms;
             if (info.lds_bytes > kLdsLimitBytes) { status = "lds"; break; }
-            auto run = [&]() {
-                return hipModuleLaunchKernel(k->fn, grid[0], grid[1], grid[2], block[0], block[1], block[2], 0, s,
-                                             argv.data(), nullptr);
-            };
-            refresh(); // a fresh copy of every argument for the verified run
-            (void)hipEventRecord(ev0.e, s);
-            if (run() != hipSuccess) { status = "launch"; break; }
-            (void)hipEventRecord(ev1.e, s);
-            bool differs = false;
-            if (verify) {
-                size_t o = 0;
-                for (auto &a : t->args) {
-                    if (a->kind != Argument::Output) continue;
-                    const int n = (int)(a->host.size() / 4);
-                    (void)sgemm_util::launch_compare(s, a->work.f(), n, a->ref.f(), n, 1, n, abs_tols[o++], rel_tol, dwords);
-                    unsigned int bits[2] = {0, 0};
-                    (void)hipMemcpyAsync(bits, dwords, 8, hipMemcpyDeviceToHost, s);
-                    if (hipStreamSynchronize(s) != hipSuccess) { hip_failure = 1; break; }
-                    if (bits[0] != 0) differs = true;
-                }
-            }
-            if (hip_failure || hipStreamSynchronize(s) != hipSuccess) { status = "fault"; hip_failure = 1; break; }
-            if (differs) { status = "verify"; ++failed_verify; break; }
-            float first = 0.0f;
-            (void)hipEventElapsedTime(&first, ev0.e, ev1.e);
-            bool was_cut = false;
-            ms = time_configuration(s, [&] { (void)run(); }, first, rules, best_ms, ev0, ev1, &samples, &was_cut);
-            if (ms < 0.0) { status = "fault"; hip_failure = 1; break; }
-            if (was_cut) { status = "ok-cut"; break; }
+            const Measured m = run_verify_time(
+                s, refresh, // a fresh copy of every argument for the verified run
+                [&] {
+                    return hipModuleLaunchKernel(k->fn, grid[0], grid[1], grid[2], block[0], block[1], block[2], 0, s,
+                                                 argv.data(), nullptr) == hipSuccess;
+                },
+                verify ? std::function<int()>([&] {
+                    bool differs = false;
+                    size_t o = 0;
+                    for (auto &a : t->args) {
+                        if (a->kind != Argument::Output) continue;
+                        const int n = (int)(a->host.size() / 4);
+                        unsigned int bits[2] = {0, 0};
+                        (void)sgemm_util::launch_compare(s, a->work.f(), n, a->ref.f(), n, 1, n, abs_tols[o++], rel_tol, dwords);
+                        (void)hipMemcpyAsync(bits, dwords, 8, hipMemcpyDeviceToHost, s);
+                        if (hipStreamSynchronize(s) != hipSuccess) return -1;
+                        if (bits[0] != 0) differs = true;
+                    }
+                    return differs ? 1 : 0;
+                }) : std::function<int()>(),
+                rules, best_ms, ev0, ev1);
+            status = m.status;
+            samples = m.samples;
+            if (m.device_failed) hip_failure = 1;
+            if (std::strcmp(m.status, "verify") == 0) ++failed_verify;
+            if (std::strcmp(m.status, "ok") != 0) { if (std::strcmp(m.status, "ok-cut") == 0) ms = m.ms; break; }
+            ms = m.ms;
             if (best_ms == 0.0 || ms < best_ms) best_ms = ms;
         } while (false);
         t->times[idx] = (float)ms;

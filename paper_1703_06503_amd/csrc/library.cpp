@@ -510,6 +510,26 @@ double time_configuration(hipStream_t s, const std::function<void()> &launch, fl
     return median(t);
 }
 
+Measured run_verify_time(hipStream_t s, const std::function<void()> &fresh_arguments,
+                         const std::function<bool()> &launch, const std::function<int()> &outputs_differ,
+                         const TimingRules &rules, double best_ms, Event &ev0, Event &ev1) {
+    Measured m;
+    if (fresh_arguments) fresh_arguments();
+    (void)hipEventRecord(ev0.e, s);
+    if (!launch()) { m.status = "launch"; return m; }
+    (void)hipEventRecord(ev1.e, s);
+    const int differ = outputs_differ ? outputs_differ() : (hipStreamSynchronize(s) == hipSuccess ? 0 : -1);
+    if (differ < 0) { m.status = "fault"; m.device_failed = true; return m; }
+    if (differ > 0) { m.status = "verify"; return m; }
+    float first = 0.0f;
+    (void)hipEventElapsedTime(&first, ev0.e, ev1.e);
+    bool was_cut = false;
+    m.ms = time_configuration(s, [&] { (void)launch(); }, first, rules, best_ms, ev0, ev1, &m.samples, &was_cut);
+    if (m.ms < 0.0) { m.status = "fault"; m.device_failed = true; return m; }
+    if (was_cut) m.status = "ok-cut";
+    return m;
+}
+
 } // namespace detail
 } // namespace sgemm
 
@@ -1028,26 +1048,24 @@ int tune_ex(int M, int N, int K, int layout, float alpha, float beta, int strate
             compile_ms_total += info.compile_ms;
             if (info.scratch_bytes > 0) { status = "spill"; break; }
             if (info.lds_bytes > kLdsLimitBytes) { status = "lds"; break; }
-            auto launch = [&]() {
-                return launch_loaded(s, *k, key.cfg, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc);
-            };
-            // fresh C for the verified run, as every configuration gets fresh arguments
-            if (beta != 0.0f) (void)sgemm_util::launch_copy2d(s, C, ldc, C0, ldc, M, N);
-            (void)hipEventRecord(ev0.e, s);
-            if (launch() != SGEMM_OK) { status = "launch"; break; }
-            (void)hipEventRecord(ev1.e, s);
-            if (verify) (void)sgemm_util::launch_compare(s, C, ldc, ref.f(), N, M, N, abs_tol, rel_tol, dwords);
-            unsigned int bits[2] = {0, 0};
-            if (verify) (void)hipMemcpyAsync(bits, dwords, 8, hipMemcpyDeviceToHost, s);
-            if (hipStreamSynchronize(s) != hipSuccess) { status = "fault"; hip_failure = 1; break; }
-            if (verify && bits[0] != 0) { status = "verify"; break; }
-            float first = 0.0f;
-            (void)hipEventElapsedTime(&first, ev0.e, ev1.e);
-            bool was_cut = false;
-            ms = time_configuration(s, [&] { (void)launch(); }, first, rules, best_ms, ev0, ev1, &samples,
-                                    &was_cut);
-            if (ms < 0.0) { status = "fault"; hip_failure = 1; break; }
-            if (was_cut) { status = "ok-cut"; break; }
+            const Measured m = run_verify_time(
+                s,
+                // fresh C for the verified run, as every configuration gets fresh arguments
+                [&] { if (beta != 0.0f) (void)sgemm_util::launch_copy2d(s, C, ldc, C0, ldc, M, N); },
+                [&] { return launch_loaded(s, *k, key.cfg, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc) == SGEMM_OK; },
+                verify ? std::function<int()>([&] {
+                    unsigned int bits[2] = {0, 0};
+                    (void)sgemm_util::launch_compare(s, C, ldc, ref.f(), N, M, N, abs_tol, rel_tol, dwords);
+                    (void)hipMemcpyAsync(bits, dwords, 8, hipMemcpyDeviceToHost, s);
+                    if (hipStreamSynchronize(s) != hipSuccess) return -1;
+                    return bits[0] != 0 ? 1 : 0;
+                }) : std::function<int()>(),
+                rules, best_ms, ev0, ev1);
+            status = m.status;
+            samples = m.samples;
+            if (m.device_failed) hip_failure = 1;
+            if (std::strcmp(m.status, "ok") != 0) { if (std::strcmp(m.status, "ok-cut") == 0) ms = m.ms; break; }
+            ms = m.ms;
             if (best_ms == 0.0 || ms < best_ms) best_ms = ms;
         } while (false);
         if (logf) {
