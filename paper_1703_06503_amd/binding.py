@@ -611,6 +611,7 @@ def ktuner_create(source, entry, global_size, local_size):
 
 def ktuner_destroy(t):
     lib().ktuner_destroy(t)
+    _ktuner_callbacks.pop(t, None)
 
 
 def ktuner_add_parameter(t, name, values):
