@@ -72,7 +72,8 @@ int conv2d_reference(void *hip_stream, int X, int Y, int Xf, int Yf, float w, co
 /* With the best configuration known for (X, Y, Xf, Yf): the one a conv2d_tune() of this process
  * or conv2d_config_set() stored; else that of the nearest image size with the same filter; else
  * a built-in default (the winner of a recorded full search with a 3 x 3, 7 x 7 or 11 x 11
- * filter, whichever is nearest in number of taps).  Never tunes.  Uses the
+ * filter, whichever is nearest in number of taps; a configuration with the filter loops kept as
+ * loops for filters of more than 121 taps).  Never tunes.  Uses the
  * stream of sgemm_set_stream(). */
 int conv2d_tuned(int X, int Y, int Xf, int Yf, float w, const float *F, const float *A, int lda,
                  float *B, int ldb);

@@ -199,13 +199,16 @@ struct TunedConv {
 std::map<std::tuple<int, int, int, int>, TunedConv> g_tuned; // Xf, Yf, X, Y
 
 // Built-in defaults: the winners of full searches on an 8192 x 4096 image with 3 x 3, 7 x 7 and
-// 11 x 11 filters, each serving the filters nearest to it in number of taps.  All three read
-// their taps through the caches (LMEM = 0), so they are valid for every filter size.
+// 11 x 11 filters, each serving the filters nearest to it in number of taps.  All read their taps
+// through the caches (LMEM = 0), so they are valid for every filter size.  Filters with more taps
+// than were ever searched get a configuration whose filter loops stay loops: fully unrolled,
+// their guarded builds run out of registers (measured on 13 x 13 to 31 x 31).
 conv2d_config default_config(int Xf, int Yf) {
     const int taps = Xf * Yf;
     if (taps <= 16) return conv2d_config{64, 8, 4, 1, 0, 1, 0, 1};
     if (taps <= 81) return conv2d_config{32, 8, 8, 2, 0, 8, 0, 1};
-    return conv2d_config{32, 8, 4, 8, 0, 4, 0, 1};
+    if (taps <= 121) return conv2d_config{32, 8, 4, 8, 0, 4, 0, 1};
+    return conv2d_config{32, 8, 4, 4, 0, 4, 0, 0};
 }
 
 // 1 = exact entry, 0 = nearest image with the same filter or the default

@@ -41,8 +41,9 @@ def conv_variants():
         todo += [(b.conv2d_space_get(Xf, Yf, i), Xf, Yf) for i in tc.sample(Xf, Yf)]
     for c in tc.CONFIGS:
         todo += [(b.make_conv_config(*c), f[0], f[1]) for f in ((7, 5), (3, 3))]
-    for f in (3, 5, 7, 11):
-        todo.append((b.conv2d_config_select(1, 1, f, f)[1], f, f))
+    b.conv2d_cache_clear()
+    for fx, fy in [(3, 3), (5, 5), (7, 7), (11, 11), (1, 1), (2, 5), (9, 9), (11, 3), (13, 13), (31, 5), (17, 17)]:
+        todo.append((b.conv2d_config_select(1, 1, fx, fy)[1], fx, fy))
     for cfg, Xf, Yf in todo:
         for edge in (0, 1):
             for vector in (0, 1):

@@ -103,6 +103,16 @@ def test_reference_kernel_matches_the_oracle():
         check(run(None, A, F, -0.5, X, Y, entry="reference"), A, F, -0.5, X, Y, what="reference")
 
 
+def test_default_dispatch_for_filter_sizes_that_were_never_tuned():
+    """conv2d_tuned with nothing in its table: the built-in defaults for small, medium, large and
+    very large filters, square and not, on a ragged image."""
+    b.conv2d_cache_clear()
+    for Xf, Yf in [(1, 1), (2, 5), (9, 9), (11, 3), (13, 13), (31, 5), (17, 17)]:
+        X, Y = 333, 77
+        A, F = synth.make_conv_inputs(X, Y, Xf, Yf, seed=90 + Xf)
+        check(run(None, A, F, 0.5, X, Y, entry="tuned"), A, F, 0.5, X, Y, what=f"default for {Xf}x{Yf}")
+
+
 def test_degenerate_sizes_and_error_returns():
     import torch
     cfg = b.make_conv_config(32, 8, 2, 4, 1, 2, 0, 1)
