@@ -4,7 +4,7 @@ library.
 The paper builds its space as the cartesian product of short per-parameter value lists,
 pruned by user constraints and by device limits (sections "Advanced usage" and "Search
 strategies and search-space properties").  This file writes out, in plain Python, the value
-lists of this build's three presets and every constraint of its GEMM kernel family, and
+lists of the library's five presets and every constraint of its GEMM kernel family, and
 enumerates the product in lexicographic order (first parameter slowest).
 
 Parameters, in order: MWG NWG KWG MDIMC NDIMC VWM VWN SA SB PAD KWI MFMA GRP SK NS.
