@@ -112,6 +112,8 @@ CONV_WORKLOADS = {
     "conv_3x3": ConvWorkload("conv_3x3", 8192, 4096, 3, 3, 1.0 / 9, 11),
     "conv_7x7": ConvWorkload("conv_7x7", 8192, 4096, 7, 7, 1.0 / 49, 12),
     "conv_11x11": ConvWorkload("conv_11x11", 8192, 4096, 11, 11, 1.0 / 121, 13),
+    # not a multiple of any workgroup tile: the guarded builds
+    "conv_7x7_ragged": ConvWorkload("conv_7x7_ragged", 8190, 4090, 7, 7, 1.0 / 49, 14),
 }
 
 

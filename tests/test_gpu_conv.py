@@ -168,10 +168,13 @@ def test_tuner_on_the_device_and_tuned_dispatch(tmp_path):
     check(run(None, A, F, 1.0, 333, 99, entry="tuned"), A, F, 1.0, 333, 99, what="conv2d_tuned default")
 
 
-@pytest.mark.parametrize("name", ["conv_3x3", "conv_7x7", "conv_11x11"])
+@pytest.mark.parametrize("name", ["conv_3x3", "conv_7x7", "conv_11x11", "conv_7x7_ragged"])
 def test_full_size_image_on_sampled_outputs(name):
-    """The paper's 8192 x 4096 image: outputs sampled over the whole image (corners, tile seams
-    and random points) against the oracle, and the whole result against the reference kernel."""
+    """The paper's 8192 x 4096 image (and one just short of it, so that interior workgroups take
+    the plain path and border workgroups the guarded one): outputs sampled over the whole image
+    (corners, tile seams and random points) against the oracle, and the whole result against
+    the reference kernel."""
+    b.conv2d_cache_clear()
     import torch
     wl = synth.CONV_WORKLOADS[name]
     A, F = synth.make_conv_workload(wl)
