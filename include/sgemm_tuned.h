@@ -166,6 +166,10 @@ typedef struct tune_result {
  * The variant is the cached best configuration for (M,N,K,layout); on a miss, the cached
  * configuration of the nearest tuned shape that is valid here, else a built-in default.
  * This call never tunes.  A variant not yet in the kernel cache is compiled on first use.
+ * Large problems whose sizes are not multiples of the tile AND whose stored rows are not
+ * multiples of the load vector go through zero-padded copies (sgemm_run_config_padded(); see
+ * sgemm_config_prefers_padding()), which then share one library workspace: such calls must not
+ * overlap in time.
  * sgemm_tuned() launches on the stream given to sgemm_set_stream() (default: null stream). */
 int sgemm_tuned(int M, int N, int K, float alpha, const float *A, int lda, const float *B,
                 int ldb, float beta, float *C, int ldc, int layout);
@@ -205,6 +209,15 @@ int sgemm_run_config(void *hip_stream, const sgemm_config *cfg, int M, int N, in
 int sgemm_run_config_padded(void *hip_stream, const sgemm_config *cfg, int M, int N, int K,
                             float alpha, const float *A, int lda, const float *B, int ldb, float beta,
                             float *C, int ldc, int layout);
+
+/* [host] Whether sgemm_tuned() / sgemm_tuned_on() would take the padded path for this call with
+ * cfg (pointers assumed 16-byte aligned): 1 when the sizes are not multiples of cfg's tile, a
+ * stored row is not a multiple of the load vector (so the guarded build would load single
+ * floats) and the problem is large enough for the copies to pay, by a model fitted to
+ * measurements (cubes from about 3800 for beta = 0, 4900 for beta != 0); else 0.  The tuner and sgemm_run_config() never pad
+ * on their own. */
+int sgemm_config_prefers_padding(const sgemm_config *cfg, int M, int N, int K, int lda, int ldb, int ldc,
+                                 int layout, float beta);
 
 /* The reference kernel every tested configuration is compared with inside tune*() (the
  * paper's result verification, section "Advanced usage"): one thread per element of C,

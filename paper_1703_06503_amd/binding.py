@@ -128,7 +128,7 @@ KTUNER_CONSTRAINT = ctypes.CFUNCTYPE(ctypes.c_int, ctypes.POINTER(ctypes.c_int),
 
 EXPORTS = (
     "sgemm_tuned", "sgemm_tuned_on", "sgemm_tuned_online", "sgemm_set_stream", "sgemm_run_config",
-    "sgemm_run_config_padded", "sgemm_reference",
+    "sgemm_run_config_padded", "sgemm_config_prefers_padding", "sgemm_reference",
     "tune", "tune_ex", "tune_replay", "sgemm_space_size", "sgemm_space_raw_size",
     "sgemm_space_get", "sgemm_space_find", "sgemm_space_dims", "sgemm_space_values",
     "sgemm_config_check", "sgemm_config_lds_bytes", "sgemm_config_default",
@@ -182,6 +182,7 @@ def lib():
         L.sgemm_set_stream.argtypes = [vp]
         L.sgemm_run_config.argtypes = [vp, cfgp] + gemm
         L.sgemm_run_config_padded.argtypes = [vp, cfgp] + gemm
+        L.sgemm_config_prefers_padding.argtypes = [cfgp, i, i, i, i, i, i, i, f]
         L.sgemm_reference.argtypes = [vp] + gemm
         L.tune.argtypes = [i, i, i, i, i]
         L.tune_ex.argtypes = [i, i, i, i, f, f, i, i, ctypes.c_ulonglong,
@@ -338,6 +339,11 @@ def sgemm_run_config_padded(stream, cfg, M, N, K, alpha, A, lda, B, ldb, beta, C
     return _check(lib().sgemm_run_config_padded(_stream(stream), ctypes.byref(cfg), M, N, K, alpha,
                                                 _ptr(A), lda, _ptr(B), ldb, beta, _ptr(C), ldc,
                                                 layout), "sgemm_run_config_padded")
+
+
+def sgemm_config_prefers_padding(cfg, M, N, K, lda, ldb, ldc, layout=0, beta=0.0):
+    return _check(lib().sgemm_config_prefers_padding(ctypes.byref(cfg), M, N, K, lda, ldb, ldc, layout,
+                                                     beta), "sgemm_config_prefers_padding")
 
 
 def sgemm_reference(stream, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, layout=0):

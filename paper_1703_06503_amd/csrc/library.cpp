@@ -608,6 +608,30 @@ int sgemm_run_config_padded(void *hip_stream, const sgemm_config *cfg, int M, in
     return SGEMM_OK;
 }
 
+// Guarded build on the operands as they are, or zero-padded copies and the unguarded build?
+// The guarded build costs little unless a stored row is not a multiple of the load vector: then
+// its loads are narrowed to single floats and it runs at about 0.86 of the unguarded rate
+// (measured 123-125 against 144-146 TFLOP/s at 4090^3 and 8190^3).  The padded path pays four
+// extra launches and copies that run at about half the HBM rate (measured 4.2 TB/s).  Padding is
+// chosen when this model says it wins by more than 3 %: from about 3800^3 upwards for
+// beta = 0 and 4900^3 for beta != 0 (just below a multiple of a 256-wide tile).
+bool prefers_padding(const sgemm_config &cfg, int M, int N, int K, const float *A, int lda, const float *B,
+                     int ldb, const float *C, int ldc, int layout, float alpha, float beta) {
+    if (M == 0 || N == 0 || K == 0 || alpha == 0.0f) return false;
+    const VariantKey key = resolve_variant(cfg, M, N, K, A, lda, B, ldb, C, ldc, layout);
+    if (!key.edge) return false;
+    const bool a_narrowed = cfg.sa && cfg.vwm >= 4 && key.cfg.vwm == 1;
+    const bool b_narrowed = cfg.sb && cfg.vwn >= 4 && key.cfg.vwn == 1;
+    if (!a_narrowed && !b_narrowed) return false;
+    const double Mp = (M + cfg.mwg - 1) / cfg.mwg * (double)cfg.mwg, Np = (N + cfg.nwg - 1) / cfg.nwg * (double)cfg.nwg,
+                 Kp = (K + cfg.kwg - 1) / cfg.kwg * (double)cfg.kwg;
+    const double t_guarded = 2.0 * M * N * (double)K / (0.86 * 145e12);
+    const double t_unguarded = 2.0 * Mp * Np * Kp / 145e12;
+    const double copied = 4.0 * (2.0 * (Mp * Kp + Kp * Np) + (beta != 0.0f ? 2.0 * Mp * Np : 0.0) + 2.0 * M * (double)N);
+    const double t_copies = copied / 4.2e12 + 12e-6;
+    return t_guarded > 1.03 * (t_unguarded + t_copies);
+}
+
 int sgemm_tuned_on(void *hip_stream, int M, int N, int K, float alpha, const float *A, int lda,
                    const float *B, int ldb, float beta, float *C, int ldc, int layout) {
     const int rc = check_gemm_args(M, N, K, A, lda, B, ldb, C, ldc, layout, alpha != 0.0f);
@@ -617,8 +641,18 @@ int sgemm_tuned_on(void *hip_stream, int M, int N, int K, float alpha, const flo
         std::lock_guard<std::mutex> lock(g_mu);
         select_config_locked(M, N, K, layout, &cfg);
     }
+    if (prefers_padding(cfg, M, N, K, A, lda, B, ldb, C, ldc, layout, alpha, beta))
+        return sgemm_run_config_padded(hip_stream, &cfg, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, layout);
     return run_config(static_cast<hipStream_t>(hip_stream), cfg, M, N, K, alpha, A, lda, B, ldb, beta,
                       C, ldc, layout);
+}
+
+int sgemm_config_prefers_padding(const sgemm_config *cfg, int M, int N, int K, int lda, int ldb, int ldc,
+                                 int layout, float beta) {
+    if (!cfg || M < 0 || N < 0 || K < 0 || layout < 0 || layout > 3) return SGEMM_E_BADARG;
+    if (violates(*cfg)) return SGEMM_E_INVALID;
+    const float *aligned = reinterpret_cast<const float *>(uintptr_t{256});
+    return prefers_padding(*cfg, M, N, K, aligned, lda, aligned, ldb, aligned, ldc, layout, 1.0f, beta) ? 1 : 0;
 }
 
 int sgemm_tuned_online(void *hip_stream, int M, int N, int K, float alpha, const float *A, int lda,

@@ -250,6 +250,30 @@ def test_padded_path_matches_the_oracle_and_leaves_padding_untouched(which, layo
     gu.check_against_oracle(out[:M, :N], A, B, Cbuf[:M, :N].copy(), 1.0, 0.5, layout)
 
 
+def test_dispatch_pads_a_large_problem_with_odd_rows_and_stays_within_the_bound():
+    """4090^3 through sgemm_tuned_on(): the committed 4096^3 winner serves it, its guarded build
+    would load single floats, so dispatch goes through zero-padded copies; sampled rows, columns
+    and scattered elements against the oracle, and the whole result against the reference kernel."""
+    import torch
+    _restore_cache()
+    M = N = K = 4090
+    cfg = b.sgemm_config_select(M, N, K, 0)
+    assert b.sgemm_config_prefers_padding(cfg, M, N, K, K, N, N, 0, 0.0) == 1
+    A, B, C = synth.make_inputs(M, N, K, 0, seed=91, dist="normal")
+    dA, dB, dC = (torch.from_numpy(x).cuda() for x in (A, B, C))
+    dR = dC.clone()
+    b.sgemm_tuned_on(None, M, N, K, 1.0, dA, K, dB, N, 0.0, dC, N, 0)
+    b.sgemm_reference(None, M, N, K, 1.0, dA, K, dB, N, 0.0, dR, N, 0)
+    torch.cuda.synchronize()
+    r, c = synth.sample_positions(M, N, 91, rows=2, cols=2, scattered=512)
+    ref = orc.sgemm_sample(1.0, A, B, 0.0, C, r, c, 0)
+    tol = orc.tolerance(K, np.abs(A).max(), np.abs(B).max(), ref)
+    got = dC.cpu().numpy()
+    assert np.all(np.abs(got[r, c] - ref) <= tol)
+    bound = 1e-5 * K * float(dA.abs().max()) * float(dB.abs().max()) + 1e-6 * dR.abs()
+    assert bool(((dC - dR).abs() <= 2 * bound).all())
+
+
 def test_degenerate_sizes():
     import torch
     cfg = _some_configs()[1]
