@@ -212,9 +212,10 @@ int sgemm_run_config_padded(void *hip_stream, const sgemm_config *cfg, int M, in
 
 /* [host] Whether sgemm_tuned() / sgemm_tuned_on() would take the padded path for this call with
  * cfg (pointers assumed 16-byte aligned): 1 when the sizes are not multiples of cfg's tile, a
- * stored row is not a multiple of the load vector (so the guarded build would load single
- * floats) and the problem is large enough for the copies to pay, by a model fitted to
- * measurements (cubes from about 3800 for beta = 0, 4900 for beta != 0); else 0.  The tuner and sgemm_run_config() never pad
+ * stored row is not a multiple of the load vector (so the guarded build would load pairs or
+ * single floats) and the problem is large enough for the copies to pay, by a model fitted to
+ * measurements (odd row lengths: cubes from about 3800 for beta = 0, 4900 for beta != 0; even
+ * row lengths keep 2-float loads and are not padded at any measured size); else 0.  The tuner and sgemm_run_config() never pad
  * on their own. */
 int sgemm_config_prefers_padding(const sgemm_config *cfg, int M, int N, int K, int lda, int ldb, int ldc,
                                  int layout, float beta);

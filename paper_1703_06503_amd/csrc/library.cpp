@@ -176,24 +176,25 @@ bool aligned_for(const void *p, int ld, int vw) {
 VariantKey resolve_variant(const sgemm_config &cfg, int M, int N, int K, const float *A, int lda,
                            const float *B, int ldb, const float *C, int ldc, int layout) {
     VariantKey key{cfg, layout, 0};
-    if (key.cfg.sa && key.cfg.vwm > 1 && !aligned_for(A, lda, key.cfg.vwm)) key.cfg.vwm = 1;
-    const bool vwn_loads_b = key.cfg.sb;
-    const bool vwn_stores_c = (key.cfg.mfma == 0);
-    // with split K the variant stores into workspace planes of M x N floats, not into C
-    const bool c_ok = splits_k(cfg, K) ? (N % key.cfg.vwn == 0 && ((long long)M * N) % key.cfg.vwn == 0)
-                                       : aligned_for(C, ldc, key.cfg.vwn);
-    if (key.cfg.vwn > 1 && ((vwn_loads_b && !aligned_for(B, ldb, key.cfg.vwn)) || (vwn_stores_c && !c_ok)))
-        key.cfg.vwn = 1;
     key.edge = (M % cfg.mwg || N % cfg.nwg || K % cfg.kwg) ? 1 : 0;
     key.splitk = splits_k(cfg, K) ? 1 : 0;
     if (key.cfg.ns == 0) key.cfg.ns = 2;
-    // a guarded tile load clamps or zeroes whole vectors, so a stored row must not end inside
-    // one; narrower LDS-direct loads mean more of them, which may not leave room for 3 or 4
-    // buffers
-    if (key.edge) {
-        if (key.cfg.sa && ((layout & 1) ? M : K) % key.cfg.vwm) key.cfg.vwm = 1;
-        if (key.cfg.sb && ((layout & 2) ? K : N) % key.cfg.vwn) key.cfg.vwn = 1;
-    }
+    // A vector width is kept only if every access it makes is aligned, and, in a guarded build,
+    // if no stored row ends inside a vector (a guarded tile load clamps or zeroes whole vectors).
+    // Otherwise it is halved until it fits; LDS-direct loads know only 4 floats or 1.
+    const int row_a = (layout & 1) ? M : K, row_b = (layout & 2) ? K : N;
+    const bool vwn_loads_b = cfg.sb != 0, vwn_stores_c = cfg.mfma == 0;
+    auto a_fits = [&](int v) { return aligned_for(A, lda, v) && (!key.edge || row_a % v == 0); };
+    auto b_fits = [&](int v) {
+        if (vwn_loads_b && !(aligned_for(B, ldb, v) && (!key.edge || row_b % v == 0))) return false;
+        if (!vwn_stores_c) return true;
+        // with split K the variant stores into workspace planes of M x N floats, not into C
+        return key.splitk ? (N % v == 0 && ((long long)M * N) % v == 0) : aligned_for(C, ldc, v);
+    };
+    if (key.cfg.sa)
+        while (key.cfg.vwm > 1 && !a_fits(key.cfg.vwm)) key.cfg.vwm = key.cfg.sa == 2 ? 1 : key.cfg.vwm / 2;
+    while (key.cfg.vwn > 1 && !b_fits(key.cfg.vwn)) key.cfg.vwn = key.cfg.sb == 2 ? 1 : key.cfg.vwn / 2;
+    // narrower LDS-direct loads mean more of them, which may not leave room for 3 or 4 buffers
     while (key.cfg.ns > 2 && (key.cfg.ns - 2) * direct_loads_per_slab(key.cfg) > kMaxLoadsInFlight)
         --key.cfg.ns;
     // narrowed loads that no longer fit the counter at all: stage through registers instead
@@ -610,22 +611,25 @@ int sgemm_run_config_padded(void *hip_stream, const sgemm_config *cfg, int M, in
 
 // Guarded build on the operands as they are, or zero-padded copies and the unguarded build?
 // The guarded build costs little unless a stored row is not a multiple of the load vector: then
-// its loads are narrowed to single floats and it runs at about 0.86 of the unguarded rate
-// (measured 123-125 against 144-146 TFLOP/s at 4090^3 and 8190^3).  The padded path pays four
-// extra launches and copies that run at about half the HBM rate (measured 4.2 TB/s).  Padding is
-// chosen when this model says it wins by more than 3 %: from about 3800^3 upwards for
-// beta = 0 and 4900^3 for beta != 0 (just below a multiple of a 256-wide tile).
+// its loads are narrowed, and with the 4096^3 winner it runs at about 0.93 of the unguarded rate
+// with 2-float loads (rows even: measured 134.5 against 144.5 TFLOP/s at 4090^3) and 0.86 with
+// single floats (rows odd: 122.7 at 4091^3).  The padded path pays four extra launches and copies
+// that run at about half the HBM rate (measured 4.2 TB/s).  Padding is chosen when this model
+// says it wins by more than 3 %: odd row lengths from about 3800^3 upwards for beta = 0 and
+// 4900^3 for beta != 0.
 bool prefers_padding(const sgemm_config &cfg, int M, int N, int K, const float *A, int lda, const float *B,
                      int ldb, const float *C, int ldc, int layout, float alpha, float beta) {
     if (M == 0 || N == 0 || K == 0 || alpha == 0.0f) return false;
     const VariantKey key = resolve_variant(cfg, M, N, K, A, lda, B, ldb, C, ldc, layout);
     if (!key.edge) return false;
-    const bool a_narrowed = cfg.sa && cfg.vwm >= 4 && key.cfg.vwm == 1;
-    const bool b_narrowed = cfg.sb && cfg.vwn >= 4 && key.cfg.vwn == 1;
-    if (!a_narrowed && !b_narrowed) return false;
+    auto rate_with = [](int wanted, int got) { return wanted < 4 || got >= 4 ? 1.0 : got == 2 ? 0.93 : 0.86; };
+    double rate = 1.0;
+    if (cfg.sa) rate = std::min(rate, rate_with(cfg.vwm, key.cfg.vwm));
+    if (cfg.sb) rate = std::min(rate, rate_with(cfg.vwn, key.cfg.vwn));
+    if (rate == 1.0) return false;
     const double Mp = (M + cfg.mwg - 1) / cfg.mwg * (double)cfg.mwg, Np = (N + cfg.nwg - 1) / cfg.nwg * (double)cfg.nwg,
                  Kp = (K + cfg.kwg - 1) / cfg.kwg * (double)cfg.kwg;
-    const double t_guarded = 2.0 * M * N * (double)K / (0.86 * 145e12);
+    const double t_guarded = 2.0 * M * N * (double)K / (rate * 145e12);
     const double t_unguarded = 2.0 * Mp * Np * Kp / 145e12;
     const double copied = 4.0 * (2.0 * (Mp * Kp + Kp * Np) + (beta != 0.0f ? 2.0 * Mp * Np : 0.0) + 2.0 * M * (double)N);
     const double t_copies = copied / 4.2e12 + 12e-6;

@@ -30,6 +30,10 @@ def fixed_config_variants():
         for layout in (0, 1, 2, 3):
             for edge in (0, 1):
                 b.sgemm_kernel_compile(cfg, layout, edge)
+        M, N, K = t.NARROW_SHAPE
+        for layout in (0, 3):
+            variant, edge = b.sgemm_kernel_resolve(cfg, M, N, K, M if layout & 1 else K, K if layout & 2 else N, N, layout)
+            b.sgemm_kernel_compile(variant, layout, edge)
 
 
 def conv_variants():

@@ -193,14 +193,20 @@ def test_per_shape_cache_roundtrip(tmp_path):
 
 
 def test_dispatch_pads_only_large_problems_with_rows_that_break_the_load_vector():
+    """Also: a row length that is even but not a multiple of 4 narrows a 4-float load to 2, not 1."""
     cfg = b.make_config(256, 256, 32, 32, 8, 4, 4, 1, 1, 0, 8, 1, 0, 1, 2)
     def pads(M, N, K, beta=0.0):
         return b.sgemm_config_prefers_padding(cfg, M, N, K, K, N, N, 0, beta)
-    assert pads(4090, 4090, 4090) == 1 and pads(8190, 8190, 8190) == 1 and pads(6142, 6142, 6142, 1.0) == 1
-    assert pads(4094, 4094, 4094, 1.0) == 0       # beta != 0 adds two copies of C: not yet worth it
+    assert pads(4091, 4091, 4091) == 1 and pads(8191, 8191, 8191) == 1 and pads(6143, 6143, 6143, 1.0) == 1
+    assert pads(4093, 4093, 4093, 1.0) == 0       # beta != 0 adds two copies of C: not yet worth it
+    assert pads(4090, 4090, 4090) == 0 and pads(8190, 8190, 8190) == 0   # even rows keep 2-float loads
     assert pads(4096, 4096, 4096) == 0            # multiples of the tile: nothing to guard
     assert pads(3000, 3000, 3000) == 0            # rows are multiples of 4: guards cost little
     assert pads(4090, 4096, 4096) == 0            # only M is ragged: no stored row is cut
-    assert pads(1022, 1022, 1022) == 0            # too small for the copies to pay
+    assert pads(1021, 1021, 1021) == 0            # too small for the copies to pay
+    v, edge = b.sgemm_kernel_resolve(cfg, 4090, 4090, 4090, 4090, 4090, 4090, 0)
+    assert (v.vwm, v.vwn, edge) == (2, 2, 1)
+    v, edge = b.sgemm_kernel_resolve(cfg, 4091, 4091, 4091, 4091, 4091, 4091, 0)
+    assert (v.vwm, v.vwn, edge) == (1, 1, 1)
     scalar = b.make_config(64, 64, 16, 8, 8, 1, 1, 1, 1, 0, 8, 0, 0, 1, 2)
-    assert b.sgemm_config_prefers_padding(scalar, 4090, 4090, 4090, 4090, 4090, 4090, 0, 0.0) == 0
+    assert b.sgemm_config_prefers_padding(scalar, 4091, 4091, 4091, 4091, 4091, 4091, 0, 0.0) == 0

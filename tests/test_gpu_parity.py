@@ -20,6 +20,7 @@ EXACT_EXT = (768, 768, 1024)      # multiples of 96, 192 and 256; 16..64 slabs t
 RAGGED_EXT = (300, 520, 1000)
 EXACT_SHAPE = (256, 512, 96)      # multiples of every tile size: unguarded variants
 RAGGED_SHAPE = (200, 136, 68)     # guarded variants, several tiles for small configs
+NARROW_SHAPE = (202, 138, 66)     # even, not multiples of 4
 RAGGED_BIG = (300, 520, 44)       # more than one tile even at 256 x 256
 
 
@@ -251,12 +252,12 @@ def test_padded_path_matches_the_oracle_and_leaves_padding_untouched(which, layo
 
 
 def test_dispatch_pads_a_large_problem_with_odd_rows_and_stays_within_the_bound():
-    """4090^3 through sgemm_tuned_on(): the committed 4096^3 winner serves it, its guarded build
+    """4091^3 through sgemm_tuned_on(): the committed 4096^3 winner serves it, its guarded build
     would load single floats, so dispatch goes through zero-padded copies; sampled rows, columns
     and scattered elements against the oracle, and the whole result against the reference kernel."""
     import torch
     _restore_cache()
-    M = N = K = 4090
+    M = N = K = 4091
     cfg = b.sgemm_config_select(M, N, K, 0)
     assert b.sgemm_config_prefers_padding(cfg, M, N, K, K, N, N, 0, 0.0) == 1
     A, B, C = synth.make_inputs(M, N, K, 0, seed=91, dist="normal")
@@ -272,6 +273,16 @@ def test_dispatch_pads_a_large_problem_with_odd_rows_and_stays_within_the_bound(
     assert np.all(np.abs(got[r, c] - ref) <= tol)
     bound = 1e-5 * K * float(dA.abs().max()) * float(dB.abs().max()) + 1e-6 * dR.abs()
     assert bool(((dC - dR).abs() <= 2 * bound).all())
+
+
+@pytest.mark.parametrize("which", WHICH)
+def test_even_sizes_that_are_not_multiples_of_four_keep_two_float_loads(which):
+    """Row lengths 138 and 66 (202 when A is stored transposed): 4-float loads are narrowed to 2."""
+    cfg = _some_configs()[which]
+    for layout in (0, 3):
+        A, B, C = synth.make_inputs(*NARROW_SHAPE, layout, seed=95 + layout)
+        got = gu.run_gpu(cfg, A, B, C, 1.25, -0.5, layout)
+        gu.check_against_oracle(got, A, B, C, 1.25, -0.5, layout, what=f"{cfg} {NARROW_SHAPE} layout {layout}")
 
 
 def test_degenerate_sizes():
