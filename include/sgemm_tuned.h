@@ -37,7 +37,9 @@ extern "C" {
 #define SGEMM_E_INVALID (-6)  /* configuration violates a constraint of the kernel family */
 #define SGEMM_E_IO (-7)       /* cache file could not be read or written */
 #define SGEMM_E_NODEVICE (-8) /* no usable HIP device */
-#define SGEMM_E_RESOURCE (-9) /* variant compiled but spills registers or exceeds LDS */
+#define SGEMM_E_RESOURCE (-9) /* variant compiled but spills registers or exceeds LDS; or a call
+                                 that may not allocate needs more scratch memory than exists */
+#define SGEMM_E_NOTREADY (-10) /* sgemm_tuned_noalloc(): this call's variant is not loaded yet */
 
 /* ---- layout bits ------------------------------------------------------------------
  * The paper's kernel multiplies A^T by B, i.e. it expects A stored K x M.  Here that
@@ -65,6 +67,8 @@ extern "C" {
 #define SGEMM_SPACE_EXT 3   /* SGEMM_SPACE_MFMA plus tile edges 96 and 192, K slabs of 64 and
                                split K (sk up to 16): for sizes that powers of two tile badly
                                and for shapes with few tiles and a long K */
+
+#define SGEMM_SPACE_CUSTOM 5 /* value lists given by the caller: sgemm_space_define_custom() */
 
 /* One point of the parameter space.  Names follow the paper's GEMM parameters (list in
  * "Tuning parameters" of the matrix-multiplication case study): the workgroup tile
@@ -168,14 +172,39 @@ typedef struct tune_result {
  * This call never tunes.  A variant not yet in the kernel cache is compiled on first use.
  * Large problems whose sizes are not multiples of the tile AND whose stored rows are not
  * multiples of the load vector go through zero-padded copies (sgemm_run_config_padded(); see
- * sgemm_config_prefers_padding()), which then share one library workspace: such calls must not
- * overlap in time.
+ * sgemm_config_prefers_padding()).
+ * Device workspaces (split-K planes, padded copies) belong to the library, one set per stream,
+ * allocated on first need and kept: calls on different streams never share one, calls on one
+ * stream are ordered by the stream.  A call whose shape, leading dimensions, pointer alignment
+ * and "beta is zero" have been seen before finds its loaded variant and launch plan by one hash
+ * lookup; the first such call resolves, loads (compiles, if need be) and plans.
  * sgemm_tuned() launches on the stream given to sgemm_set_stream() (default: null stream). */
 int sgemm_tuned(int M, int N, int K, float alpha, const float *A, int lda, const float *B,
                 int ldb, float beta, float *C, int ldc, int layout);
 int sgemm_tuned_on(void *hip_stream, int M, int N, int K, float alpha, const float *A, int lda,
                    const float *B, int ldb, float beta, float *C, int ldc, int layout);
 int sgemm_set_stream(void *hip_stream);
+
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): the same operation and the same variant as
+ * sgemm_tuned_on(), with no hipMalloc, hipFree, module load or other allocating call inside.
+ *   - The call must have been prepared: an earlier sgemm_tuned_on() call with the same M, N, K,
+ *     layout, leading dimensions, pointer alignment (16 / 8 / 4 bytes, per operand) and the same
+ *     "beta == 0" has loaded the variant.  Otherwise SGEMM_E_NOTREADY and nothing is launched.
+ *   - Split-K planes lie in a statically allocated device array of SGEMM_NOALLOC_SCRATCH_BYTES
+ *     (one per GPU, held until the process ends) instead of an allocated workspace.  A call whose
+ *     planes (parts * M * N floats, see sgemm_config_workspace_bytes()) do not fit returns
+ *     SGEMM_E_RESOURCE and launches nothing.  Every plane element that is read is written by the
+ *     same call first, so nothing needs clearing between calls.
+ *   - Zero-padded copies are never used: sizes that are not multiples of the tile run the
+ *     guarded build (same result within rounding).
+ *   - All calls on one GPU share that GPU's array: calls that split K and overlap in time (on
+ *     different streams) race.  Order them, or use sgemm_tuned_on() for all but one stream.
+ *   - The first call on a device looks up the array's device address (no allocation, but not
+ *     capturable): make one call outside any graph capture first. */
+#define SGEMM_NOALLOC_SCRATCH_BYTES (32u << 20)
+int sgemm_tuned_noalloc(void *hip_stream, int M, int N, int K, float alpha, const float *A, int lda,
+                        const float *B, int ldb, float beta, float *C, int ldc, int layout);
 
 /* The same call with on-line tuning (the paper's other mode of use: tuning "at run time, in the
  * first calls", section "CLTune: an auto-tuner for OpenCL kernels").  While (M,N,K,layout) has
@@ -205,7 +234,7 @@ int sgemm_run_config(void *hip_stream, const sgemm_config *cfg, int M, int N, in
  * sizes are multiples of cfg's tile, the unguarded build runs on those, and the M x N result is
  * copied back into C.  Same result as sgemm_run_config() within rounding (the padding adds exact
  * zeros); four extra kernels and (|A| + |B| + 2|C|) of extra traffic.  Sizes that already are
- * multiples take the ordinary path.  Calls that overlap in time must not both use it. */
+ * multiples take the ordinary path.  The workspace belongs to the stream of the call. */
 int sgemm_run_config_padded(void *hip_stream, const sgemm_config *cfg, int M, int N, int K,
                             float alpha, const float *A, int lda, const float *B, int ldb, float beta,
                             float *C, int ldc, int layout);
@@ -246,6 +275,16 @@ int tune_replay(int space, const float *ms_table, int table_len, int strategy, i
                 tune_result *out);
 
 /* ---- search space [host] ------------------------------------------------------------- */
+/* Define SGEMM_SPACE_CUSTOM, the counterpart of the paper's AddParameter(name, {values}) for this
+ * kernel family ("CLTune: an auto-tuner for OpenCL kernels"): `spec` is HOST text of the form
+ * "MWG=64,128 NWG=128 KWG=32,64 SK=4,8" - parameter names as in sgemm_config (upper case),
+ * separated by blanks or ';'.  A parameter that is not named keeps one value (MWG=NWG=128 KWG=32
+ * MDIMC=NDIMC=16 VWM=VWN=4 SA=SB=1 PAD=1 KWI=8 MFMA=1 GRP=0 SK=1 NS=2).  The product is pruned by
+ * the kernel family's constraints like every preset.  Returns the number of valid
+ * configurations (>= 0) or SGEMM_E_BADARG.  A process that never calls this reads the
+ * definition from $SGEMM_TUNED_CUSTOM_SPACE on first use.  Redefining the space while a search
+ * over it runs is safe; that search finishes on the old definition. */
+int sgemm_space_define_custom(const char *spec);
 int sgemm_space_size(int space);      /* valid configurations after constraint pruning     */
 long long sgemm_space_raw_size(int space); /* plain product of the value-list lengths      */
 int sgemm_space_get(int space, int index, sgemm_config *out);

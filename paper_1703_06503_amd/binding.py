@@ -12,10 +12,11 @@ LIB_PATH = os.path.join(HERE, "lib", "libsgemm_tuned.so")
 
 OK = 0
 E_BADARG, E_NOCONFIG, E_COMPILE, E_LAUNCH, E_VERIFY = -1, -2, -3, -4, -5
-E_INVALID, E_IO, E_NODEVICE, E_RESOURCE = -6, -7, -8, -9
+E_INVALID, E_IO, E_NODEVICE, E_RESOURCE, E_NOTREADY = -6, -7, -8, -9, -10
 LAYOUT_A_TRANSPOSED, LAYOUT_B_TRANSPOSED = 1, 2
 STRATEGY_FULL, STRATEGY_RANDOM, STRATEGY_ANNEALING, STRATEGY_PSO = 0, 1, 2, 3
-SPACE_FULL, SPACE_SMALL, SPACE_MFMA, SPACE_EXT, SPACE_DIRECT = 0, 1, 2, 3, 4
+SPACE_FULL, SPACE_SMALL, SPACE_MFMA, SPACE_EXT, SPACE_DIRECT, SPACE_CUSTOM = 0, 1, 2, 3, 4, 5
+NOALLOC_SCRATCH_BYTES = 32 << 20
 
 CONFIG_FIELDS = ("mwg", "nwg", "kwg", "mdimc", "ndimc", "vwm", "vwn", "sa", "sb", "pad", "kwi",
                  "mfma", "grp", "sk", "ns")
@@ -127,9 +128,9 @@ KTUNER_CONSTRAINT = ctypes.CFUNCTYPE(ctypes.c_int, ctypes.POINTER(ctypes.c_int),
 
 
 EXPORTS = (
-    "sgemm_tuned", "sgemm_tuned_on", "sgemm_tuned_online", "sgemm_set_stream", "sgemm_run_config",
+    "sgemm_tuned", "sgemm_tuned_on", "sgemm_tuned_noalloc", "sgemm_tuned_online", "sgemm_set_stream", "sgemm_run_config",
     "sgemm_run_config_padded", "sgemm_config_prefers_padding", "sgemm_reference",
-    "tune", "tune_ex", "tune_replay", "sgemm_space_size", "sgemm_space_raw_size",
+    "tune", "tune_ex", "tune_replay", "sgemm_space_define_custom", "sgemm_space_size", "sgemm_space_raw_size",
     "sgemm_space_get", "sgemm_space_find", "sgemm_space_dims", "sgemm_space_values",
     "sgemm_config_check", "sgemm_config_lds_bytes", "sgemm_config_default",
     "sgemm_config_workspace_bytes",
@@ -178,6 +179,7 @@ def lib():
         gemm = [i, i, i, f, vp, i, vp, i, f, vp, i, i]
         L.sgemm_tuned.argtypes = gemm
         L.sgemm_tuned_on.argtypes = [vp] + gemm
+        L.sgemm_tuned_noalloc.argtypes = [vp] + gemm
         L.sgemm_tuned_online.argtypes = [vp] + gemm + [i, i, i]
         L.sgemm_set_stream.argtypes = [vp]
         L.sgemm_run_config.argtypes = [vp, cfgp] + gemm
@@ -190,6 +192,7 @@ def lib():
         L.tune_replay.argtypes = [i, ctypes.POINTER(f), i, i, i, ctypes.c_ulonglong,
                                   ctypes.POINTER(tune_opts), ctypes.POINTER(i), i,
                                   ctypes.POINTER(tune_result)]
+        L.sgemm_space_define_custom.argtypes = [ctypes.c_char_p]
         L.sgemm_space_size.argtypes = [i]
         L.sgemm_space_raw_size.argtypes = [i]
         L.sgemm_space_raw_size.restype = ctypes.c_longlong
@@ -318,6 +321,11 @@ def sgemm_tuned_on(stream, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, layout=
                                        ldb, beta, _ptr(C), ldc, layout), "sgemm_tuned_on")
 
 
+def sgemm_tuned_noalloc(stream, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, layout=0):
+    return _check(lib().sgemm_tuned_noalloc(_stream(stream), M, N, K, alpha, _ptr(A), lda, _ptr(B),
+                                            ldb, beta, _ptr(C), ldc, layout), "sgemm_tuned_noalloc")
+
+
 def sgemm_tuned_online(stream, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, layout=0,
                        space=SPACE_MFMA, strategy=STRATEGY_ANNEALING, budget=32):
     return _check(lib().sgemm_tuned_online(_stream(stream), M, N, K, alpha, _ptr(A), lda, _ptr(B),
@@ -374,6 +382,11 @@ def tune_replay(space, ms_table, strategy, budget, seed=0, opts=None):
                                   ctypes.byref(opts) if opts is not None else None, visited, n,
                                   ctypes.byref(res)), "tune_replay")
     return ev, res, list(visited[:ev])
+
+
+def sgemm_space_define_custom(spec):
+    """Number of valid configurations of the newly defined SPACE_CUSTOM."""
+    return _check(lib().sgemm_space_define_custom(spec.encode()), "sgemm_space_define_custom")
 
 
 def sgemm_space_size(space):

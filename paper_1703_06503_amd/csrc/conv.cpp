@@ -463,7 +463,11 @@ int conv2d_tune(int X, int Y, int Xf, int Yf, float w, int strategy, int budget,
             if (info.scratch_bytes > 0) { status = "spill"; break; }
             if (info.lds_bytes > kLdsLimitBytes) { status = "lds"; break; }
             const Measured m = run_verify_time(
-                s, nullptr, [&] { return launch(s, *k, v, X, Y, w, dF.f(), dA.f(), lda, dB.f(), ldb) == SGEMM_OK; },
+                s,
+                // fresh output for the verified run: a NaN in every element, so that an output the
+                // variant fails to write cannot pass for the previous variant's correct value
+                [&] { if (verify) (void)sgemm_util::launch_fill_bits(s, dB.f(), Y, X, ldb, 0x7fc00000u); },
+                [&] { return launch(s, *k, v, X, Y, w, dF.f(), dA.f(), lda, dB.f(), ldb) == SGEMM_OK; },
                 verify ? std::function<int()>([&] {
                     unsigned int bits[2] = {0, 0};
                     (void)sgemm_util::launch_compare(s, dB.f(), ldb, ref.f(), X, Y, X, abs_tol, rel_tol, dwords);

@@ -17,6 +17,7 @@
 #include <string>
 #include <thread>
 #include <tuple>
+#include <unordered_map>
 #include <vector>
 
 #include "../../include/sgemm_tuned.h"
@@ -45,6 +46,40 @@ struct Tuned {
 using ShapeKey = std::tuple<int, int, int, int>; // M, N, K, layout
 std::map<ShapeKey, Tuned> g_tuned;
 bool g_tuned_autoloaded = false;
+
+// What a call of sgemm_tuned_on() needs once it has been seen before: the loaded variant and
+// its launch plan, found by one hash lookup on integers.  The key holds everything the choice
+// depends on: sizes, storage layout, leading dimensions, how far each pointer is aligned (16,
+// 8 or 4 bytes: what decides the load vectors), and whether beta is zero (part of the
+// pad-or-guard decision).  Entries are dropped whenever the per-shape table changes.
+struct DispatchKey {
+    int M, N, K, layout, lda, ldb, ldc, flags;
+    bool operator==(const DispatchKey &o) const { return std::memcmp(this, &o, sizeof *this) == 0; }
+};
+struct DispatchKeyHash {
+    size_t operator()(const DispatchKey &k) const {
+        uint64_t h = 1469598103934665603ull;
+        const int *v = &k.M;
+        for (int i = 0; i < 8; ++i) { h ^= (uint64_t)(uint32_t)v[i]; h *= 1099511628211ull; }
+        return (size_t)h;
+    }
+};
+struct Dispatch {
+    std::shared_ptr<LoadedKernel> kernel; // the build that runs on the operands as they are
+    sgemm_config chosen;                  // what the per-shape table selected
+    int tiles_m = 0, tiles_n = 0;         // grid of workgroup tiles over C
+    int parts = 1, k_chunk = 0;           // split K as it applies to this K
+    bool padded = false;                  // sgemm_tuned_on() goes through zero-padded copies
+};
+std::unordered_map<DispatchKey, Dispatch, DispatchKeyHash> g_dispatch;
+constexpr size_t kMaxDispatch = 4096;
+
+void tuned_table_changed_locked() { g_dispatch.clear(); }
+
+int align_class(const void *p) {
+    const uintptr_t a = (uintptr_t)p;
+    return (a % 16 == 0) ? 2 : (a % 8 == 0) ? 1 : 0;
+}
 
 std::string library_dir() {
     Dl_info info;
@@ -78,6 +113,7 @@ int load_cache_file_locked(const char *path) {
         ++added;
     }
     std::fclose(f);
+    tuned_table_changed_locked();
     return added;
 }
 
@@ -135,7 +171,11 @@ int select_config_locked(int M, int N, int K, int layout, sgemm_config *out) {
     autoload_locked();
     auto it = g_tuned.find(ShapeKey{M, N, K, layout});
     if (it != g_tuned.end()) { *out = it->second.cfg; return SGEMM_OK; }
-    // nearest tuned shape of the same layout, by distance between the logarithms of the sizes
+    // nearest tuned shape of the same layout, by distance between the logarithms of the sizes.
+    // A configuration is only lent to shapes like the one it was tuned for (every size within
+    // about a factor of 1.5, or one size within a factor of 2.3): beyond that its tile and
+    // above all its split K fit the other shape no better than the built-in rule does.
+    constexpr double kNearEnough = 1.5;
     double best = -1.0;
     for (auto &kv : g_tuned) {
         if (std::get<3>(kv.first) != layout) continue;
@@ -143,7 +183,7 @@ int select_config_locked(int M, int N, int K, int layout, sgemm_config *out) {
         const double dn = std::log2((double)std::max(N, 1)) - std::log2((double)std::max(std::get<1>(kv.first), 1));
         const double dk = std::log2((double)std::max(K, 1)) - std::log2((double)std::max(std::get<2>(kv.first), 1));
         const double d = dm * dm + dn * dn + dk * dk;
-        if (best < 0.0 || d < best) { best = d; *out = kv.second.cfg; }
+        if (d <= kNearEnough && (best < 0.0 || d < best)) { best = d; *out = kv.second.cfg; }
     }
     if (best >= 0.0) return SGEMM_OK;
     *out = default_config(M, N, K);
@@ -206,86 +246,73 @@ VariantKey resolve_variant(const sgemm_config &cfg, int M, int N, int K, const f
     return key;
 }
 
-// Device workspace for split K: the partial planes and one arrival counter per tile of C.
-// One per process, grown on demand and kept.  The counters are zeroed when allocated and every
-// launch leaves them at zero again (the last part of a tile resets its counter).  Calls that
-// overlap in time on different streams and both split K would share the workspace, so such
-// calls must be ordered by the caller (the same rule as for any single-workspace library).
-float *g_workspace = nullptr;
-size_t g_workspace_floats = 0;
-unsigned int *g_counters = nullptr;
-size_t g_counters_count = 0;
+// Device workspaces: the split-K planes and the zero-padded copies of the pad-and-run path.
+// One set per (device, stream), grown on demand and kept, so calls on different streams never
+// share a buffer and calls on one stream are ordered by the stream itself.  hipFree waits for
+// the device, so a buffer is never released under a kernel that still uses it.  At most
+// kMaxWorkspaces sets are kept; the one unused for longest is released for a new stream.
+struct StreamWorkspace {
+    float *planes = nullptr;
+    size_t plane_floats = 0;
+    float *pad = nullptr;
+    size_t pad_floats = 0;
+    uint64_t last_use = 0;
+};
+std::map<std::pair<int, hipStream_t>, StreamWorkspace> g_workspaces;
+uint64_t g_workspace_clock = 0;
+constexpr size_t kMaxWorkspaces = 8;
 
-int workspace_for(size_t floats, size_t tiles, float **planes, unsigned int **counters) {
-    std::lock_guard<std::mutex> lock(g_mu);
-    if (floats > g_workspace_floats) {
-        // hipFree waits for the device, so no kernel is still using the old buffer
-        if (g_workspace) (void)hipFree(g_workspace);
-        g_workspace = nullptr;
-        g_workspace_floats = 0;
-        void *p = nullptr;
-        const size_t want = std::max(floats, (size_t)(8u << 20)); // at least 32 MiB
-        const hipError_t e = hipMalloc(&p, want * sizeof(float));
-        if (e != hipSuccess) {
-            set_error(std::string("hipMalloc of the split-K workspace: ") + hipGetErrorString(e));
-            return SGEMM_E_LAUNCH;
+StreamWorkspace *stream_workspace_locked(hipStream_t s) {
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    const auto key = std::make_pair(dev, s);
+    auto it = g_workspaces.find(key);
+    if (it == g_workspaces.end()) {
+        if (g_workspaces.size() >= kMaxWorkspaces) {
+            auto oldest = g_workspaces.begin();
+            for (auto j = g_workspaces.begin(); j != g_workspaces.end(); ++j)
+                if (j->second.last_use < oldest->second.last_use) oldest = j;
+            if (oldest->second.planes) (void)hipFree(oldest->second.planes);
+            if (oldest->second.pad) (void)hipFree(oldest->second.pad);
+            g_workspaces.erase(oldest);
         }
-        g_workspace = static_cast<float *>(p);
-        g_workspace_floats = want;
+        it = g_workspaces.emplace(key, StreamWorkspace{}).first;
     }
-    if (tiles > g_counters_count) {
-        if (g_counters) (void)hipFree(g_counters);
-        g_counters = nullptr;
-        g_counters_count = 0;
-        void *p = nullptr;
-        const size_t want = std::max(tiles, (size_t)65536);
-        hipError_t e = hipMalloc(&p, want * sizeof(unsigned int));
-        if (e == hipSuccess) e = hipMemset(p, 0, want * sizeof(unsigned int));
-        if (e != hipSuccess) {
-            set_error(std::string("hipMalloc of the split-K counters: ") + hipGetErrorString(e));
-            if (p) (void)hipFree(p);
-            return SGEMM_E_LAUNCH;
-        }
-        g_counters = static_cast<unsigned int *>(p);
-        g_counters_count = want;
+    it->second.last_use = ++g_workspace_clock;
+    return &it->second;
+}
+
+int grow_locked(float **buf, size_t *have, size_t want, size_t at_least, const char *what) {
+    if (want <= *have) return SGEMM_OK;
+    if (*buf) (void)hipFree(*buf);
+    *buf = nullptr;
+    *have = 0;
+    void *p = nullptr;
+    const size_t n = std::max(want, at_least);
+    const hipError_t e = hipMalloc(&p, n * sizeof(float));
+    if (e != hipSuccess) {
+        set_error(std::string("hipMalloc of the ") + what + ": " + hipGetErrorString(e));
+        return SGEMM_E_LAUNCH;
     }
-    *planes = g_workspace;
-    *counters = g_counters;
+    *buf = static_cast<float *>(p);
+    *have = n;
     return SGEMM_OK;
 }
 
-// Second device workspace, for the zero-padded copies of A, B and C of sgemm_run_config_padded().
-float *g_pad_workspace = nullptr;
-size_t g_pad_workspace_floats = 0;
-
-int pad_workspace_for(size_t floats, float **out) {
+int workspace_for(hipStream_t s, size_t floats, float **planes) {
     std::lock_guard<std::mutex> lock(g_mu);
-    if (floats > g_pad_workspace_floats) {
-        if (g_pad_workspace) (void)hipFree(g_pad_workspace);
-        g_pad_workspace = nullptr;
-        g_pad_workspace_floats = 0;
-        void *p = nullptr;
-        const hipError_t e = hipMalloc(&p, floats * sizeof(float));
-        if (e != hipSuccess) {
-            set_error(std::string("hipMalloc of the padding workspace: ") + hipGetErrorString(e));
-            return SGEMM_E_LAUNCH;
-        }
-        g_pad_workspace = static_cast<float *>(p);
-        g_pad_workspace_floats = floats;
-    }
-    *out = g_pad_workspace;
-    return SGEMM_OK;
+    StreamWorkspace *w = stream_workspace_locked(s);
+    const int rc = grow_locked(&w->planes, &w->plane_floats, floats, (size_t)(8u << 20), "split-K workspace");
+    *planes = w->planes;
+    return rc;
 }
 
-// How the planes of a split-K launch are added up: by default a second kernel does it;
-// SGEMM_TUNED_SPLITK=fused lets the last workgroup of each tile do it inside the GEMM launch
-// (same result bit for bit; measured equally fast, so the simpler way is the default).
-bool split_two_pass() {
-    static const bool v = [] {
-        const char *e = std::getenv("SGEMM_TUNED_SPLITK");
-        return !(e && std::strcmp(e, "fused") == 0);
-    }();
-    return v;
+int pad_workspace_for(hipStream_t s, size_t floats, float **out) {
+    std::lock_guard<std::mutex> lock(g_mu);
+    StreamWorkspace *w = stream_workspace_locked(s);
+    const int rc = grow_locked(&w->pad, &w->pad_floats, floats, 0, "padding workspace");
+    *out = w->pad;
+    return rc;
 }
 
 // How a configuration's SK is applied to a problem: `parts` workgroups per tile, each summing
@@ -305,41 +332,48 @@ SplitPlan plan_split(const sgemm_config &cfg, int K) {
 
 bool splits_k(const sgemm_config &cfg, int K) { return plan_split(cfg, K).parts > 1; }
 
-int launch_loaded(hipStream_t s, const LoadedKernel &k, const sgemm_config &cfg, int M, int N, int K,
-                  float alpha, const float *A, int lda, const float *B, int ldb, float beta, float *C,
-                  int ldc) {
-    int tiles_m = (M + cfg.mwg - 1) / cfg.mwg;
-    int tiles_n = (N + cfg.nwg - 1) / cfg.nwg;
+// One launch of a loaded variant with its plan worked out: tiles_m x tiles_n tiles of C, `parts`
+// workgroups per tile that each sum k_chunk consecutive k into their own plane of `planes`
+// (parts * M * N floats of device memory; unused and may be null when parts == 1), followed by
+// the reduction kernel when K is split.
+int launch_planned(hipStream_t s, const LoadedKernel &k, int tiles_m, int tiles_n, int parts, int k_chunk,
+                   float *planes, int M, int N, int K, float alpha, const float *A, int lda, const float *B,
+                   int ldb, float beta, float *C, int ldc) {
     const long long wgs = (long long)tiles_m * tiles_n;
     if (wgs > 0x7fffffffll) return SGEMM_E_BADARG;
-    const SplitPlan plan = plan_split(cfg, K);
-    int k_chunk = plan.k_chunk;
-    float *planes = nullptr;
-    unsigned int *counters = nullptr;
-    if (plan.parts > 1) {
-        // every part writes its raw sum into its own plane; the last part of a tile (or the
-        // reduction kernel) adds them up and applies alpha and beta
-        const int rc = workspace_for((size_t)plan.parts * (size_t)M * (size_t)N, (size_t)wgs, &planes, &counters);
-        if (rc != SGEMM_OK) return rc;
-        if (split_two_pass()) counters = nullptr;
-    }
-    void *args[] = {&M, &N, &K, &alpha, &A, &lda, &B, &ldb, &beta, &C, &ldc, &tiles_m, &tiles_n,
-                    &k_chunk, &planes, &counters};
-    const hipError_t e = hipModuleLaunchKernel(k.fn, (unsigned)wgs, (unsigned)plan.parts, 1,
-                                               (unsigned)k.threads, 1, 1, 0, s, args, nullptr);
+    void *args[] = {&M, &N, &K, &alpha, &A, &lda, &B, &ldb, &beta, &C, &ldc, &tiles_m, &tiles_n, &k_chunk, &planes};
+    static const unsigned dyn_lds = [] { // experiment: unused dynamic LDS caps the workgroups per CU
+        const char *e = std::getenv("SGEMM_TUNED_EXPERIMENT_DYN_LDS");
+        return e ? (unsigned)std::atoi(e) : 0u;
+    }();
+    const hipError_t e = hipModuleLaunchKernel(k.fn, (unsigned)wgs, (unsigned)parts, 1, (unsigned)k.threads, 1, 1,
+                                               dyn_lds, s, args, nullptr);
     if (e != hipSuccess) {
         set_error(std::string("hipModuleLaunchKernel: ") + hipGetErrorString(e));
         return SGEMM_E_LAUNCH;
     }
-    if (plan.parts > 1 && counters == nullptr) {
-        const hipError_t r = sgemm_util::launch_splitk_reduce(s, M, N, plan.parts, planes, (size_t)M * (size_t)N,
-                                                              alpha, beta, C, ldc);
+    if (parts > 1) {
+        const hipError_t r = sgemm_util::launch_splitk_reduce(s, M, N, parts, planes, (size_t)M * (size_t)N, alpha,
+                                                              beta, C, ldc);
         if (r != hipSuccess) {
             set_error(std::string("split-K reduction: ") + hipGetErrorString(r));
             return SGEMM_E_LAUNCH;
         }
     }
     return SGEMM_OK;
+}
+
+int launch_loaded(hipStream_t s, const LoadedKernel &k, const sgemm_config &cfg, int M, int N, int K,
+                  float alpha, const float *A, int lda, const float *B, int ldb, float beta, float *C,
+                  int ldc) {
+    const SplitPlan plan = plan_split(cfg, K);
+    float *planes = nullptr;
+    if (plan.parts > 1) {
+        const int rc = workspace_for(s, (size_t)plan.parts * (size_t)M * (size_t)N, &planes);
+        if (rc != SGEMM_OK) return rc;
+    }
+    return launch_planned(s, k, (M + cfg.mwg - 1) / cfg.mwg, (N + cfg.nwg - 1) / cfg.nwg, plan.parts, plan.k_chunk,
+                          planes, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc);
 }
 
 int get_loaded(const VariantKey &key, std::shared_ptr<LoadedKernel> *out) {
@@ -549,7 +583,8 @@ const char *sgemm_status_string(int status) {
     case SGEMM_E_INVALID: return "configuration violates a constraint";
     case SGEMM_E_IO: return "cache file i/o failed";
     case SGEMM_E_NODEVICE: return "no HIP device";
-    case SGEMM_E_RESOURCE: return "variant spills registers or exceeds LDS";
+    case SGEMM_E_RESOURCE: return "variant spills registers or exceeds LDS, or scratch memory too small";
+    case SGEMM_E_NOTREADY: return "call not prepared (no allocation allowed)";
     default: return status > 0 ? "count" : "unknown status";
     }
 }
@@ -588,7 +623,7 @@ int sgemm_run_config_padded(void *hip_stream, const sgemm_config *cfg, int M, in
     const int bp_rows = (layout & 2) ? Np : Kp, bp_cols = (layout & 2) ? Kp : Np;
     const size_t na = (size_t)ap_rows * ap_cols, nb = (size_t)bp_rows * bp_cols, nc = (size_t)Mp * Np;
     float *ws = nullptr;
-    rc = pad_workspace_for(na + nb + nc, &ws);
+    rc = pad_workspace_for(s, na + nb + nc, &ws);
     if (rc != SGEMM_OK) return rc;
     float *Ap = ws, *Bp = ws + na, *Cp = ws + na + nb;
     hipError_t e = sgemm_util::launch_pad_copy(s, Ap, ap_cols, ap_rows, ap_cols, A, lda, a_rows, a_cols);
@@ -636,20 +671,103 @@ bool prefers_padding(const sgemm_config &cfg, int M, int N, int K, const float *
     return t_guarded > 1.03 * (t_unguarded + t_copies);
 }
 
-int sgemm_tuned_on(void *hip_stream, int M, int N, int K, float alpha, const float *A, int lda,
-                   const float *B, int ldb, float beta, float *C, int ldc, int layout) {
-    const int rc = check_gemm_args(M, N, K, A, lda, B, ldb, C, ldc, layout, alpha != 0.0f);
-    if (rc != SGEMM_OK) return rc;
-    sgemm_config cfg;
+// The slow half of a dispatch: choose the configuration, decide between the guarded build and
+// zero-padded copies, resolve and load the variant, work out the launch plan.
+static int build_dispatch(int M, int N, int K, float alpha, const float *A, int lda, const float *B, int ldb,
+                          float beta, const float *C, int ldc, int layout, Dispatch *d) {
     {
         std::lock_guard<std::mutex> lock(g_mu);
-        select_config_locked(M, N, K, layout, &cfg);
+        select_config_locked(M, N, K, layout, &d->chosen);
     }
-    if (prefers_padding(cfg, M, N, K, A, lda, B, ldb, C, ldc, layout, alpha, beta))
-        return sgemm_run_config_padded(hip_stream, &cfg, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, layout);
-    return run_config(static_cast<hipStream_t>(hip_stream), cfg, M, N, K, alpha, A, lda, B, ldb, beta,
-                      C, ldc, layout);
+    d->padded = prefers_padding(d->chosen, M, N, K, A, lda, B, ldb, C, ldc, layout, alpha, beta);
+    const VariantKey key = resolve_variant(d->chosen, M, N, K, A, lda, B, ldb, C, ldc, layout);
+    const int rc = get_loaded(key, &d->kernel);
+    if (rc != SGEMM_OK) return rc;
+    const SplitPlan plan = plan_split(key.cfg, K);
+    d->tiles_m = (M + key.cfg.mwg - 1) / key.cfg.mwg;
+    d->tiles_n = (N + key.cfg.nwg - 1) / key.cfg.nwg;
+    d->parts = plan.parts;
+    d->k_chunk = plan.k_chunk;
+    return SGEMM_OK;
 }
+
+// Shared by sgemm_tuned_on() and sgemm_tuned_noalloc().  `may_allocate` = false: a call that
+// has not been seen before (its variant would have to be loaded) is an error, zero-padded copies
+// are never used, and the split-K planes lie in the library's static device array.
+static int dispatch_call(hipStream_t s, int M, int N, int K, float alpha, const float *A, int lda, const float *B,
+                         int ldb, float beta, float *C, int ldc, int layout, bool may_allocate) {
+    const int rc0 = check_gemm_args(M, N, K, A, lda, B, ldb, C, ldc, layout, alpha != 0.0f);
+    if (rc0 != SGEMM_OK) return rc0;
+    if (M == 0 || N == 0) return SGEMM_OK;
+    if (K == 0 || alpha == 0.0f) {
+        if (beta == 1.0f) return SGEMM_OK;
+        return sgemm_util::launch_scale(s, M, N, beta, C, ldc) == hipSuccess ? SGEMM_OK : SGEMM_E_LAUNCH;
+    }
+    const DispatchKey key{M, N, K, layout, lda, ldb, ldc,
+                          align_class(A) | (align_class(B) << 2) | (align_class(C) << 4) | (beta == 0.0f ? 64 : 0)};
+    Dispatch d;
+    bool hit;
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        auto it = g_dispatch.find(key);
+        hit = it != g_dispatch.end();
+        if (hit) d = it->second;
+    }
+    if (!hit) {
+        if (!may_allocate) {
+            set_error("this call has not been prepared: make the same call (sizes, leading dimensions, storage "
+                      "layout, pointer alignment, beta zero or not) once through sgemm_tuned_on() first");
+            return SGEMM_E_NOTREADY;
+        }
+        const int rc = build_dispatch(M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, layout, &d);
+        if (rc != SGEMM_OK) return rc;
+        std::lock_guard<std::mutex> lock(g_mu);
+        if (g_dispatch.size() >= kMaxDispatch) g_dispatch.clear();
+        g_dispatch[key] = d;
+    }
+    float *planes = nullptr;
+    if (may_allocate) {
+        if (d.padded)
+            return sgemm_run_config_padded(s, &d.chosen, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, layout);
+        if (d.parts > 1) {
+            const int rc = workspace_for(s, (size_t)d.parts * (size_t)M * (size_t)N, &planes);
+            if (rc != SGEMM_OK) return rc;
+        }
+    } else if (d.parts > 1) {
+        const size_t need = (size_t)d.parts * (size_t)M * (size_t)N;
+        if (need > sgemm_util::kScratchFloats) {
+            char msg[256];
+            std::snprintf(msg, sizeof msg,
+                          "split K of this call needs %d planes of %d x %d floats = %zu bytes, more than the %zu "
+                          "bytes of static device scratch memory: use sgemm_tuned_on()",
+                          d.parts, M, N, need * sizeof(float), sgemm_util::kScratchFloats * sizeof(float));
+            set_error(msg);
+            return SGEMM_E_RESOURCE;
+        }
+        const hipError_t e = sgemm_util::scratch_of_current_device(&planes);
+        if (e != hipSuccess) {
+            set_error(std::string("address of the static scratch array: ") + hipGetErrorString(e));
+            return SGEMM_E_LAUNCH;
+        }
+    }
+    return launch_planned(s, *d.kernel, d.tiles_m, d.tiles_n, d.parts, d.k_chunk, planes, M, N, K, alpha, A, lda, B,
+                          ldb, beta, C, ldc);
+}
+
+int sgemm_tuned_on(void *hip_stream, int M, int N, int K, float alpha, const float *A, int lda,
+                   const float *B, int ldb, float beta, float *C, int ldc, int layout) {
+    return dispatch_call(static_cast<hipStream_t>(hip_stream), M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, layout,
+                         true);
+}
+
+int sgemm_tuned_noalloc(void *hip_stream, int M, int N, int K, float alpha, const float *A, int lda,
+                        const float *B, int ldb, float beta, float *C, int ldc, int layout) {
+    return dispatch_call(static_cast<hipStream_t>(hip_stream), M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, layout,
+                         false);
+}
+
+static_assert(sgemm_util::kScratchFloats * sizeof(float) == SGEMM_NOALLOC_SCRATCH_BYTES,
+              "the header states the size of the static scratch array");
 
 int sgemm_config_prefers_padding(const sgemm_config *cfg, int M, int N, int K, int lda, int ldb, int ldc,
                                  int layout, float beta) {
@@ -755,6 +873,7 @@ int sgemm_tuned_online(void *hip_stream, int M, int N, int K, float alpha, const
             select_config_locked(M, N, K, layout, &fallback);
             g_tuned[ShapeKey{M, N, K, layout}] = Tuned{fallback, 0.0f};
         }
+        tuned_table_changed_locked();
     }
     {
         std::lock_guard<std::mutex> lock(g_online_mu);
@@ -784,6 +903,11 @@ int sgemm_reference(void *hip_stream, int M, int N, int K, float alpha, const fl
 }
 
 /* ---- search space ------------------------------------------------------------------- */
+
+int sgemm_space_define_custom(const char *spec) {
+    const int n = define_custom_space(spec);
+    return n < 0 ? SGEMM_E_BADARG : n;
+}
 
 int sgemm_space_size(int space) {
     const Space *s = get_space(space);
@@ -911,6 +1035,7 @@ int sgemm_config_set(int M, int N, int K, int layout, const sgemm_config *cfg, f
     std::lock_guard<std::mutex> lock(g_mu);
     autoload_locked();
     g_tuned[ShapeKey{M, N, K, layout}] = Tuned{*cfg, ms};
+    tuned_table_changed_locked();
     return SGEMM_OK;
 }
 
@@ -949,6 +1074,7 @@ int sgemm_cache_clear(void) {
     std::lock_guard<std::mutex> lock(g_mu);
     g_tuned_autoloaded = true; // an explicit clear also drops the auto-loaded entries
     g_tuned.clear();
+    tuned_table_changed_locked();
     return SGEMM_OK;
 }
 
@@ -1089,7 +1215,12 @@ int tune_ex(int M, int N, int K, int layout, float alpha, float beta, int strate
             const Measured m = run_verify_time(
                 s,
                 // fresh C for the verified run, as every configuration gets fresh arguments
-                [&] { if (beta != 0.0f) (void)sgemm_util::launch_copy2d(s, C, ldc, C0, ldc, M, N); },
+                // (beta == 0: C is not an input, so it is filled with NaN instead - an element the
+                // variant fails to write must not pass for the previous variant's correct value)
+                [&] {
+                    if (beta != 0.0f) (void)sgemm_util::launch_copy2d(s, C, ldc, C0, ldc, M, N);
+                    else if (verify) (void)sgemm_util::launch_fill_bits(s, C, M, N, ldc, 0x7fc00000u);
+                },
                 [&] { return launch_loaded(s, *k, key.cfg, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc) == SGEMM_OK; },
                 verify ? std::function<int()>([&] {
                     unsigned int bits[2] = {0, 0};
@@ -1143,6 +1274,7 @@ int tune_ex(int M, int N, int K, int layout, float alpha, float beta, int strate
         auto it = g_tuned.find(ShapeKey{M, N, K, layout});
         if (it == g_tuned.end() || !(it->second.ms > 0) || r.best_cost < it->second.ms)
             g_tuned[ShapeKey{M, N, K, layout}] = Tuned{from_point(space->configs[r.best_index]), (float)r.best_cost};
+        tuned_table_changed_locked();
     }
     return r.evaluations;
 }

@@ -1,5 +1,6 @@
 #include "space.h"
 
+#include <cstdlib>
 #include <mutex>
 
 namespace sgemm {
@@ -196,17 +197,101 @@ static Space build(int preset) {
     return s;
 }
 
+// ---- the caller-defined space ---------------------------------------------------------------
+// "NAME=v,v,... NAME=v ..." (names as in dim_name(), separated by blanks or ';'); a parameter
+// that is not named keeps the single value given as its default here.
+static const int kCustomDefaults[kDims] = {128, 128, 32, 16, 16, 4, 4, 1, 1, 1, 8, 1, 0, 1, 2};
+
+static bool parse_custom(const std::string &spec, std::vector<std::vector<int>> *values) {
+    values->assign(kDims, {});
+    size_t pos = 0;
+    while (pos < spec.size()) {
+        while (pos < spec.size() && (spec[pos] == ' ' || spec[pos] == ';' || spec[pos] == '\n' || spec[pos] == '\t')) ++pos;
+        if (pos >= spec.size()) break;
+        const size_t eq = spec.find('=', pos);
+        if (eq == std::string::npos) return false;
+        const std::string name = spec.substr(pos, eq - pos);
+        int dim = -1;
+        for (int d = 0; d < kDims; ++d)
+            if (name == kNames[d]) dim = d;
+        if (dim < 0 || !(*values)[dim].empty()) return false; // unknown or repeated name
+        pos = eq + 1;
+        for (;;) {
+            size_t end = pos;
+            while (end < spec.size() && spec[end] >= '0' && spec[end] <= '9') ++end;
+            if (end == pos || end - pos > 6) return false;
+            (*values)[dim].push_back(std::atoi(spec.substr(pos, end - pos).c_str()));
+            pos = end;
+            if (pos < spec.size() && spec[pos] == ',') { ++pos; continue; }
+            break;
+        }
+    }
+    for (int d = 0; d < kDims; ++d)
+        if ((*values)[d].empty()) (*values)[d].push_back(kCustomDefaults[d]);
+    return true;
+}
+
+static Space enumerate_values(int preset, std::vector<std::vector<int>> values) {
+    Space s;
+    s.preset = preset;
+    s.values = std::move(values);
+    s.raw = 1;
+    for (auto &v : s.values) s.raw *= (long long)v.size();
+    Point p{};
+    std::array<size_t, kDims> it{};
+    bool done = false;
+    while (!done) {
+        for (int d = 0; d < kDims; ++d) p[d] = s.values[d][it[d]];
+        if (violates(from_point(p)) == nullptr) {
+            s.index.emplace(Space::key(p), (int)s.configs.size());
+            s.configs.push_back(p);
+        }
+        int d = kDims - 1;
+        while (d >= 0 && ++it[d] == s.values[d].size()) { it[d] = 0; --d; }
+        if (d < 0) done = true;
+    }
+    return s;
+}
+
+static std::mutex g_space_mu;
+static std::unordered_map<int, Space *> g_built;
+
+int define_custom_space(const char *spec) {
+    std::vector<std::vector<int>> values;
+    if (!spec || !parse_custom(spec, &values)) return -1;
+    long long raw = 1;
+    for (auto &v : values) {
+        raw *= (long long)v.size();
+        if (raw > 50000000ll) return -1; // enumeration is a plain walk of the product
+    }
+    Space *fresh = new Space(enumerate_values(SGEMM_SPACE_CUSTOM, std::move(values)));
+    std::lock_guard<std::mutex> lock(g_space_mu);
+    // an earlier definition is kept alive: searches still running may hold a pointer to it
+    g_built[SGEMM_SPACE_CUSTOM] = fresh;
+    return (int)fresh->configs.size();
+}
+
 const Space *get_space(int preset) {
-    static std::mutex mu;
-    static std::unordered_map<int, Space *> built;
-    std::lock_guard<std::mutex> lock(mu);
-    auto it = built.find(preset);
-    if (it != built.end()) return it->second;
+    {
+        std::lock_guard<std::mutex> lock(g_space_mu);
+        auto it = g_built.find(preset);
+        if (it != g_built.end()) return it->second;
+    }
+    if (preset == SGEMM_SPACE_CUSTOM) {
+        // not defined by a call: the environment may define it (worker processes that compile a
+        // space in parallel learn it this way)
+        const char *env = std::getenv("SGEMM_TUNED_CUSTOM_SPACE");
+        if (!env || define_custom_space(env) < 0) return nullptr;
+        std::lock_guard<std::mutex> lock(g_space_mu);
+        return g_built[SGEMM_SPACE_CUSTOM];
+    }
     Space s = build(preset);
     if (s.preset < 0) return nullptr;
     Space *keep = new Space(std::move(s));
-    built.emplace(preset, keep);
-    return keep;
+    std::lock_guard<std::mutex> lock(g_space_mu);
+    auto ins = g_built.emplace(preset, keep);
+    if (!ins.second) delete keep;
+    return ins.first->second;
 }
 
 } // namespace sgemm

@@ -16,8 +16,8 @@ namespace sgemm {
 constexpr int kDims = 15;              // tuned fields of sgemm_config, in field order
 constexpr int kLdsLimitBytes = 163840; // LDS per workgroup on gfx950
 constexpr int kMaxThreads = 1024;
-constexpr int kMaxSplitK = 64;
-constexpr int kMaxLoadsInFlight = 63;  // the vmcnt counter of a wave         // upper bound of the SK parameter
+constexpr int kMaxSplitK = 64;         // upper bound of the SK parameter
+constexpr int kMaxLoadsInFlight = 63;  // the vmcnt counter of a wave
 
 using Point = std::array<int, kDims>;
 
@@ -46,7 +46,12 @@ struct Space {
     static uint64_t key(const Point &p);
 };
 
-// Built once per preset and kept; nullptr for an unknown preset.
+// Built once per preset and kept; nullptr for an unknown preset (or the custom one before it
+// has been defined).
 const Space *get_space(int preset);
+
+// Defines SGEMM_SPACE_CUSTOM from "NAME=v,v,... NAME=v ..."; returns the number of valid
+// configurations, or -1 when the text cannot be read.
+int define_custom_space(const char *spec);
 
 } // namespace sgemm

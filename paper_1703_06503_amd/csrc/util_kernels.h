@@ -29,6 +29,16 @@ hipError_t launch_conv2d_reference(hipStream_t s, int X, int Y, int Xf, int Yf, 
 // dst (rows_d x cols_d) = src (rows_s x cols_s) in the top-left corner, zeros elsewhere.
 hipError_t launch_pad_copy(hipStream_t s, float *dst, int ldd, int rows_d, int cols_d,
                            const float *src, int lds_, int rows_s, int cols_s);
+// Every element of a rows x cols matrix = the float with this bit pattern.
+hipError_t launch_fill_bits(hipStream_t s, float *dst, int rows, int cols, int ld, unsigned int bits);
+
+// The library's statically allocated device scratch memory (kScratchFloats floats, 256-byte
+// aligned, one copy per GPU, contents kept between calls): *ptr receives its address on the
+// current device.  The first call on a device looks the address up; no call allocates.
+constexpr size_t kScratchFloats = (size_t)8 << 20; // 32 MiB
+constexpr int kMaxDevices = 64;
+hipError_t scratch_of_current_device(float **ptr);
+
 hipError_t launch_copy2d(hipStream_t s, float *dst, int ldd, const float *src, int lds_, int rows,
                          int cols);
 

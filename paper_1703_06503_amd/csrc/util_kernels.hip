@@ -3,6 +3,8 @@
 // check, |x| maximum, and the C = beta*C scaling used when alpha == 0 or K == 0.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "util_kernels.h"
 
 namespace {
@@ -169,10 +171,25 @@ __global__ void conv2d_reference_kernel(int X, int Y, int Xf, int Yf, float w,
     B[(size_t)y * ldb + x] = w * acc;
 }
 
+// Every element of an M x N matrix (leading dimension ld) gets the same bit pattern: the
+// sentinel (a NaN) that an output holds before a configuration's verified run, so that an
+// element the variant fails to write cannot pass for the previous variant's correct value.
+__global__ void fill_bits_kernel(float *__restrict__ dst, int rows, int cols, int ld, unsigned int bits) {
+    const size_t n = (size_t)rows * cols;
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < n;
+         e += (size_t)gridDim.x * blockDim.x)
+        dst[(e / cols) * ld + e % cols] = __uint_as_float(bits);
+}
+
 __global__ void zero_u32_kernel(unsigned int *p, int n) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = 0u;
 }
+
+// Device memory that exists without any allocation call: the split-K planes of
+// sgemm_tuned_noalloc().  One copy per GPU, held until the process ends.  Host code never uses
+// this name as an address; it asks the runtime for the array's device address (below).
+static __device__ __align__(256) float scratch[sgemm_util::kScratchFloats];
 
 inline int grid_for(size_t n, int block) {
     size_t g = (n + block - 1) / block;
@@ -247,6 +264,32 @@ hipError_t launch_splitk_reduce(hipStream_t s, int M, int N, int planes, const f
                            planes, P, plane, alpha, beta, C, ldc);
     }
     return hipGetLastError();
+}
+
+hipError_t launch_fill_bits(hipStream_t s, float *dst, int rows, int cols, int ld, unsigned int bits) {
+    const size_t n = (size_t)rows * cols;
+    if (n == 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_bits_kernel, dim3(grid_for(n, 256)), dim3(256), 0, s, dst, rows, cols, ld, bits);
+    return hipGetLastError();
+}
+
+hipError_t scratch_of_current_device(float **ptr) {
+    static std::mutex mu;
+    static float *known[kMaxDevices] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!known[dev]) {
+        // each GPU holds its own copy of the array at its own address
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        known[dev] = static_cast<float *>(p);
+    }
+    *ptr = known[dev];
+    return hipSuccess;
 }
 
 hipError_t launch_conv2d_reference(hipStream_t s, int X, int Y, int Xf, int Yf, float w, const float *F,

@@ -17,7 +17,13 @@ def _work(args):
     for i in range(lo, hi, step):
         cfg = b.sgemm_space_get(space, i)
         try:
-            info = b.sgemm_kernel_compile(cfg, layout, edge)
+            if isinstance(edge, tuple):     # a problem shape: the build a call of that shape loads
+                M, N, K = edge
+                cfg, e = b.sgemm_kernel_resolve(cfg, M, N, K, M if layout & 1 else K, K if layout & 2 else N,
+                                                N, layout)
+            else:
+                e = edge
+            info = b.sgemm_kernel_compile(cfg, layout, e)
             n_new += 0 if info.from_cache else 1
         except b.SgemmError:
             n_fail += 1
@@ -53,9 +59,18 @@ def main(argv=None):
     ap.add_argument("--layouts", default="0")
     ap.add_argument("--edge", default="0")
     ap.add_argument("--jobs", type=int, default=8)
+    ap.add_argument("--shape", default=None,
+                    help="M,N,K: compile for each configuration the build that a call of this shape "
+                         "loads (guarded or not, load vectors narrowed where rows demand it, the "
+                         "split-K build where K is split) instead of --edge")
+    ap.add_argument("--values", default=None,
+                    help='value lists of the caller-defined space (--space 5), e.g. "MWG=64,128 SK=4,8"')
     a = ap.parse_args(argv)
-    new, fail = precompile(a.space, [int(x) for x in a.layouts.split(",")],
-                           [int(x) for x in a.edge.split(",")], a.jobs)
+    if a.values:
+        import os
+        os.environ["SGEMM_TUNED_CUSTOM_SPACE"] = a.values      # the worker processes read it
+    edges = [tuple(int(x) for x in a.shape.split(","))] if a.shape else [int(x) for x in a.edge.split(",")]
+    new, fail = precompile(a.space, [int(x) for x in a.layouts.split(",")], edges, a.jobs)
     print(f"compiled {new} variants, {fail} failed")
     return 1 if fail else 0
 

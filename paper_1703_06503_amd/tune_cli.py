@@ -12,7 +12,7 @@ import sys
 import time
 
 STRATEGIES = {"full": 0, "random": 1, "annealing": 2, "pso": 3}
-SPACES = {"full": 0, "small": 1, "mfma": 2, "ext": 3, "direct": 4}
+SPACES = {"full": 0, "small": 1, "mfma": 2, "ext": 3, "direct": 4, "custom": 5}
 
 
 def main(argv=None):
@@ -20,6 +20,8 @@ def main(argv=None):
     ap.add_argument("--workload", required=True)
     ap.add_argument("--strategy", choices=sorted(STRATEGIES), default="pso")
     ap.add_argument("--space", choices=sorted(SPACES), default="full")
+    ap.add_argument("--values", default=None,
+                    help='value lists of --space custom, e.g. "MWG=64,128 NWG=128 SK=4,8"')
     ap.add_argument("--budget", type=int, default=0)
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--reps", type=int, default=0)
@@ -53,6 +55,10 @@ def main(argv=None):
     if a.start_config:
         start = b.make_config(*[int(x) for x in a.start_config.split(",")])
         b.sgemm_config_set(w.M, w.N, w.K, w.layout, start, 0.0)   # time unknown: any result replaces it
+    if a.space == "custom":
+        if not a.values:
+            ap.error("--space custom needs --values")
+        print(f"custom space: {b.sgemm_space_define_custom(a.values)} valid configurations", file=sys.stderr)
     opts = b.tune_opts()
     opts.space = SPACES[a.space]
     opts.reps = a.reps

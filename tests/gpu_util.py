@@ -7,13 +7,6 @@ from oracle import sgemm_oracle as orc
 from paper_1703_06503_amd import binding as b
 
 
-def sample_configs(space, count, seed):
-    """A fixed pseudo-random sample of configuration indices of a space (sorted)."""
-    n = b.sgemm_space_size(space)
-    rng = np.random.default_rng(seed)
-    return sorted(int(i) for i in rng.choice(n, size=min(count, n), replace=False))
-
-
 def run_gpu(cfg, A, B, C, alpha, beta, layout=0, entry="config"):
     """C_out (numpy float32) of one call through the C ABI; A, B, C are host arrays in stored
     shapes.  entry = "config" -> sgemm_run_config(cfg), "tuned" -> sgemm_tuned,

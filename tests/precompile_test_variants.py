@@ -1,83 +1,113 @@
-"""Put every kernel variant that tests/test_gpu_parity.py launches into the on-disk kernel
-cache, in parallel and without a GPU, so that the GPU run spends no time compiling:
+"""Put every kernel variant that the GPU tests, smoke() and bench.py launch into the on-disk
+kernel cache, in parallel worker processes and without a GPU (the kernel generator needs none),
+so that a GPU run compiles nothing:
 
-    python tests/precompile_test_variants.py
+    python tests/precompile_test_variants.py [jobs]
 
-(The tests pass without this step; they then compile each variant on first use.)"""
+Variants already in the cache are skipped, so a second run costs seconds.  (The tests also pass
+without this step; they then compile each variant on first use.)"""
 import os
 import sys
 
 sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
 
 from paper_1703_06503_amd import binding as b            # noqa: E402
-from tests import test_gpu_parity as t                   # noqa: E402
+from tests import variants as v                          # noqa: E402
+
+PLANTED_BUG = "-DPLANT_SKIP_TILE=1"   # tests/test_gpu_parity.py: verification must notice it
 
 
-def tuned_table_variants():
-    """The variants that sgemm_tuned() launches for the shapes of the committed table of tuned
-    configurations (what bench.py, smoke() and the full-size tests run)."""
-    from paper_1703_06503_amd import report
+def _gemm(cfg, layout, edge, extra=""):
+    return ("gemm", cfg.as_tuple(), layout, edge, extra)
+
+
+def _resolved(cfg, M, N, K, layout):
+    """The build a call with cfg launches for these sizes (dense operands, aligned pointers)."""
+    lda, ldb = (M if layout & 1 else K), (K if layout & 2 else N)
+    variant, edge = b.sgemm_kernel_resolve(cfg, M, N, K, lda, ldb, N, layout)
+    return _gemm(variant, layout, edge)
+
+
+def gemm_tasks():
+    from paper_1703_06503_amd import report, synth
+    tasks = []
+    # the committed table of tuned configurations: what sgemm_tuned() launches for its shapes
     table = os.path.join(os.path.dirname(b.LIB_PATH), "..", "tuned_configs.txt")
+    b.sgemm_cache_clear()
+    b.sgemm_cache_load(table)
     for M, N, K, layout, _ms, cfg in report.read_table(table):
-        c = b.make_config(*cfg)
-        edge = 1 if (M % c.mwg or N % c.nwg or K % c.kwg) else 0
-        b.sgemm_kernel_compile(c, layout, edge)
+        tasks.append(_resolved(b.make_config(*cfg), M, N, K, layout))
+    # configurations run at the benchmark sizes beside the winners
+    for name in ("cfg4_4096", "cfg2_2048", "cfg3_1000", "cfg3_1536"):
+        w = synth.WORKLOADS[name]
+        tasks += [_resolved(cfg, w.M, w.N, w.K, w.layout) for cfg in v.BENCH_CONFIGS]
+    for name in ("cfg5_128x4096x4096", "cfg5_4096x64x9216"):
+        w = synth.WORKLOADS[name]
+        tasks += [_resolved(cfg, w.M, w.N, w.K, w.layout) for cfg in v.SKINNY_CONFIGS]
+    # dispatch without an exactly tuned shape; the pad-and-run path loads the unguarded build
+    for M, N, K, layout in v.DISPATCHED_CALLS + [c[:4] for c in v.NOALLOC_CALLS]:
+        cfg = b.sgemm_config_select(M, N, K, layout)
+        tasks += [_resolved(cfg, M, N, K, layout), _gemm(cfg, layout, 0)]
+    (M, N, K, layout), cfg = v.NOALLOC_TOO_BIG
+    tasks.append(_resolved(cfg, M, N, K, layout))
+    # the hand-picked configurations, in every layout, guarded and not, and narrowed
+    for cfg in v.some_configs():
+        tasks += [_gemm(cfg, layout, edge) for layout in (0, 1, 2, 3) for edge in (0, 1)]
+        tasks += [_resolved(cfg, *v.NARROW_SHAPE, layout) for layout in (0, 3)]
+        for shape in [(97, 83, 45), (130, 70, 33), (1, 1, 1), (5, 300, 2), (200, 100, 300), (150, 140, 60),
+                      (192, 160, 192), (384, 256, 512), (300, 200, 150)]:
+            tasks.append(_resolved(cfg, *shape, 0))
+    # the sweeps: which build a case loads depends on the sizes too
+    for space, idx, shape, layout in v.all_sweeps():
+        tasks += [_resolved(b.sgemm_space_get(space, i), *shape, layout) for i in idx]
+    # the small space: the tuner tests search it on several shapes, once with the planted bug
+    for i in range(b.sgemm_space_size(b.SPACE_SMALL)):
+        cfg = b.sgemm_space_get(b.SPACE_SMALL, i)
+        tasks.append(_gemm(cfg, 0, 0, PLANTED_BUG))
+        tasks += [_resolved(cfg, *shape, 0) for shape in [(192, 160, 96), (256, 256, 128), (320, 256, 192)]]
+    return tasks
 
 
-def fixed_config_variants():
-    """The hand-picked configurations of the parity tests, in every layout, guarded and not."""
-    for cfg in t._some_configs():
-        for layout in (0, 1, 2, 3):
-            for edge in (0, 1):
-                b.sgemm_kernel_compile(cfg, layout, edge)
-        M, N, K = t.NARROW_SHAPE
-        for layout in (0, 3):
-            variant, edge = b.sgemm_kernel_resolve(cfg, M, N, K, M if layout & 1 else K, K if layout & 2 else N, N, layout)
-            b.sgemm_kernel_compile(variant, layout, edge)
-
-
-def conv_variants():
+def conv_tasks():
     """The convolution variants of tests/test_gpu_conv.py: guarded and unguarded, with and
     without vector accesses (which of the four a call uses depends on sizes and alignment)."""
-    from tests import test_gpu_conv as tc
     todo = []
-    for (Xf, Yf) in tc.SAMPLES:
-        todo += [(b.conv2d_space_get(Xf, Yf, i), Xf, Yf) for i in tc.sample(Xf, Yf)]
-    for c in tc.CONFIGS:
+    for (Xf, Yf) in v.CONV_SAMPLES:
+        todo += [(b.conv2d_space_get(Xf, Yf, i), Xf, Yf) for i in v.conv_sample(Xf, Yf)]
+    for c in v.CONV_CONFIGS:
         todo += [(b.make_conv_config(*c), f[0], f[1]) for f in ((7, 5), (3, 3))]
     b.conv2d_cache_clear()
-    for fx, fy in [(3, 3), (5, 5), (7, 7), (11, 11), (1, 1), (2, 5), (9, 9), (11, 3), (13, 13), (31, 5), (17, 17)]:
+    for fx, fy in v.CONV_DEFAULT_FILTERS:
         todo.append((b.conv2d_config_select(1, 1, fx, fy)[1], fx, fy))
-    for cfg, Xf, Yf in todo:
-        for edge in (0, 1):
-            for vector in (0, 1):
-                b.conv2d_kernel_compile(cfg, Xf, Yf, edge, vector)
+    return [("conv", cfg.as_tuple(), Xf, Yf, edge, vector)
+            for cfg, Xf, Yf in todo for edge in (0, 1) for vector in (0, 1)]
 
 
-def _resolve_and_compile(task):
-    space, index, (M, N, K), layout = task
-    cfg = b.sgemm_space_get(space, index)
-    lda = M if layout & 1 else K
-    ldb = K if layout & 2 else N
-    variant, edge = b.sgemm_kernel_resolve(cfg, M, N, K, lda, ldb, N, layout)
-    return 0 if b.sgemm_kernel_compile(variant, layout, edge).from_cache else 1
+def _compile(task):
+    """1 if the variant was compiled now, 0 if it was in the cache already."""
+    if task[0] == "gemm":
+        _, cfg, layout, edge, extra = task
+        if extra:
+            os.environ["SGEMM_TUNED_EXTRA_DEFINES"] = extra
+        else:
+            os.environ.pop("SGEMM_TUNED_EXTRA_DEFINES", None)
+        info = b.sgemm_kernel_compile(b.make_config(*cfg), layout, edge)
+    else:
+        _, cfg, Xf, Yf, edge, vector = task
+        info = b.conv2d_kernel_compile(b.make_conv_config(*cfg), Xf, Yf, edge, vector)
+    return 0 if info.from_cache else 1
 
 
-def sweep_variants(jobs):
-    """Exactly the build each case of the parity sweeps loads: which one that is depends on the
-    sizes too (vector widths are narrowed where a stored row is not a multiple of them)."""
+def main(jobs=None, verbose=True):
     import multiprocessing as mp
-    tasks = [(space, i, shape, layout) for space, idx, shape, layout in t.all_sweeps() for i in idx]
+    jobs = jobs or min(8, os.cpu_count() or 1)
+    tasks = sorted(set(gemm_tasks() + conv_tasks()))
     with mp.get_context("spawn").Pool(jobs) as pool:
-        new = sum(pool.map(_resolve_and_compile, tasks, chunksize=8))
-    print(f"parity sweeps: {len(tasks)} cases, {new} variants compiled now", flush=True)
+        new = sum(pool.map(_compile, tasks, chunksize=4))
+    if verbose:
+        print(f"kernel cache: {len(tasks)} variants wanted, {new} compiled now", flush=True)
+    return len(tasks), new
 
 
-def main():
-    jobs = min(8, os.cpu_count() or 1)
-    tuned_table_variants()
-    fixed_config_variants()
-    conv_variants()
-    sweep_variants(jobs)
 if __name__ == "__main__":
-    main()
+    main(int(sys.argv[1]) if len(sys.argv) > 1 else None)

@@ -33,7 +33,7 @@ def test_every_declared_symbol_is_exported_and_bound():
 
 def test_status_strings():
     assert b.sgemm_status_string(0) == "ok"
-    for code in range(-9, 0):
+    for code in range(-10, 0):
         assert b.sgemm_status_string(code) not in ("ok", "unknown status")
     assert b.sgemm_status_string(-99) == "unknown status"
 
@@ -210,3 +210,36 @@ def test_dispatch_pads_only_large_problems_with_rows_that_break_the_load_vector(
     assert (v.vwm, v.vwn, edge) == (1, 1, 1)
     scalar = b.make_config(64, 64, 16, 8, 8, 1, 1, 1, 1, 0, 8, 0, 0, 1, 2)
     assert b.sgemm_config_prefers_padding(scalar, 4091, 4091, 4091, 4091, 4091, 4091, 0, 0.0) == 0
+
+
+def test_a_tuned_configuration_is_only_lent_to_shapes_like_its_own():
+    """Dispatch on a miss: the nearest tuned shape of the same storage layout serves a call only
+    when the shapes are alike; otherwise the built-in rule plans tile and split K for the
+    actual sizes.  The A-transposed table holds two skinny split-K shapes only: a cube in
+    that layout must not inherit their split K."""
+    table = os.path.join(os.path.dirname(b.LIB_PATH), "..", "tuned_configs.txt")
+    b.sgemm_cache_clear()
+    b.sgemm_cache_load(table)
+    try:
+        skinny = b.sgemm_config_get(128, 4096, 4096, 1)
+        assert skinny is not None and skinny.sk > 1
+        cube = b.sgemm_config_select(4096, 4096, 4096, 1)
+        assert cube.as_tuple() == b.sgemm_config_default(4096, 4096, 4096, 1).as_tuple()
+        assert cube.sk == 1
+        assert b.sgemm_config_workspace_bytes(cube, 4096, 4096, 4096)[0] == 0
+        # a shape close to the tuned one still borrows its configuration
+        assert b.sgemm_config_select(128, 4000, 4200, 1).as_tuple() == skinny.as_tuple()
+        assert b.sgemm_config_select(160, 3072, 4096, 1).as_tuple() == skinny.as_tuple()
+        # and the exact shape gets its own
+        assert b.sgemm_config_select(128, 4096, 4096, 1).as_tuple() == skinny.as_tuple()
+    finally:
+        b.sgemm_cache_clear()
+        b.sgemm_cache_load(table)
+
+
+def test_noalloc_entry_point_checks_its_arguments_like_the_others():
+    with pytest.raises(b.SgemmError) as e:
+        b.sgemm_tuned_noalloc(0, 4, 4, 4, 1.0, 1, 4, 1, 4, 0.0, None, 4, 0)
+    assert e.value.status == b.E_BADARG
+    assert b.sgemm_tuned_noalloc(0, 0, 4, 4, 1.0, 0, 4, 0, 4, 0.0, 0, 4, 0) == 0   # empty: no-op
+    assert b.sgemm_status_string(b.E_NOTREADY) not in ("ok", "unknown status")

@@ -10,14 +10,7 @@ from paper_1703_06503_amd import synth
 
 pytestmark = pytest.mark.gpu
 
-SAMPLES = {(3, 3): (24, 1), (7, 7): (40, 2), (11, 11): (24, 3), (5, 3): (16, 4), (4, 2): (12, 5)}
-
-
-def sample(Xf, Yf):
-    count, seed = SAMPLES[(Xf, Yf)]
-    n = b.conv2d_space_size(Xf, Yf)
-    rng = np.random.default_rng(seed)
-    return sorted(int(i) for i in rng.choice(n, size=count, replace=False))
+from tests.variants import CONV_SAMPLES as SAMPLES, CONV_CONFIGS as CONFIGS, conv_sample as sample  # noqa: E402
 
 
 def run(cfg, A, F, w, X, Y, entry="config", ldb=None, a_offset=0):
@@ -64,11 +57,6 @@ def test_sampled_configurations_match_the_oracle(Xf, Yf):
             cfg = b.conv2d_space_get(Xf, Yf, i)
             got = run(cfg, A, F, 0.37, X, Y)
             check(got, A, F, 0.37, X, Y, what=f"{cfg} {Xf}x{Yf} on {X}x{Y}")
-
-
-CONFIGS = [(32, 8, 1, 8, 0, 1, 0, 1), (32, 16, 2, 4, 2, 2, 1, 1), (32, 8, 2, 4, 1, 2, 0, 1),
-           (16, 16, 4, 2, 2, 4, 0, 0), (64, 8, 8, 1, 2, 8, 0, 1), (8, 8, 1, 1, 1, 1, 1, 0),
-           (64, 16, 4, 4, 1, 4, 1, 0), (8, 64, 8, 8, 0, 8, 0, 1)]
 
 
 @pytest.mark.parametrize("which", range(len(CONFIGS)))

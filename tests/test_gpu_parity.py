@@ -10,38 +10,12 @@ from tests import gpu_util as gu
 
 pytestmark = pytest.mark.gpu
 
-# The fixed sample of the full space that the parity tests walk (also what
-# `tests/precompile_test_variants.py` puts into the kernel cache ahead of time).
-FULL_SAMPLE = dict(space=b.SPACE_FULL, count=160, seed=1234)
-MFMA_SAMPLE = dict(space=b.SPACE_MFMA, count=80, seed=4321)
-EXT_SAMPLE = dict(space=b.SPACE_EXT, count=80, seed=777)   # tile edges 96/192, split K
-DIRECT_SAMPLE = dict(space=b.SPACE_DIRECT, count=80, seed=555)   # LDS-direct staging, 2-4 buffers
-EXACT_EXT = (768, 768, 1024)      # multiples of 96, 192 and 256; 16..64 slabs to split
-RAGGED_EXT = (300, 520, 1000)
-EXACT_SHAPE = (256, 512, 96)      # multiples of every tile size: unguarded variants
-RAGGED_SHAPE = (200, 136, 68)     # guarded variants, several tiles for small configs
-NARROW_SHAPE = (202, 138, 66)     # even, not multiples of 4
-RAGGED_BIG = (300, 520, 44)       # more than one tile even at 256 x 256
-
-
-def all_sweeps():
-    """(space, configuration indices, shape, layout) of every sweep below: what
-    tests/precompile_test_variants.py puts into the kernel cache."""
-    full, mfma = gu.sample_configs(**FULL_SAMPLE), gu.sample_configs(**MFMA_SAMPLE)
-    ext, direct = gu.sample_configs(**EXT_SAMPLE), gu.sample_configs(**DIRECT_SAMPLE)
-    out = [(b.SPACE_SMALL, list(range(16)), (256, 256, 256), 0),
-           (b.SPACE_FULL, full, EXACT_SHAPE, 0), (b.SPACE_FULL, full, RAGGED_SHAPE, 0),
-           (b.SPACE_MFMA, mfma, EXACT_SHAPE, 0), (b.SPACE_MFMA, mfma, RAGGED_BIG, 0),
-           (b.SPACE_EXT, ext, EXACT_EXT, 0), (b.SPACE_EXT, ext, RAGGED_EXT, 0),
-           (b.SPACE_DIRECT, direct, EXACT_EXT, 0), (b.SPACE_DIRECT, direct, RAGGED_EXT, 0),
-           (b.SPACE_DIRECT, direct[::4], (203, 137, 67), 0)]
-    for layout in (1, 2, 3):
-        d = gu.sample_configs(b.SPACE_DIRECT, 24, seed=300 + layout)
-        out += [(b.SPACE_DIRECT, d, EXACT_EXT, layout), (b.SPACE_DIRECT, d, RAGGED_EXT, layout),
-                (b.SPACE_EXT, gu.sample_configs(b.SPACE_EXT, 24, seed=200 + layout), RAGGED_EXT, layout)]
-        f = gu.sample_configs(b.SPACE_FULL, 40, seed=100 + layout)
-        out += [(b.SPACE_FULL, f, EXACT_SHAPE, layout), (b.SPACE_FULL, f, RAGGED_SHAPE, layout)]
-    return out
+# The fixed samples of the spaces, the shapes and the hand-picked configurations live in
+# tests/variants.py (also read by tests/precompile_test_variants.py).
+from tests.variants import (FULL_SAMPLE, MFMA_SAMPLE, EXT_SAMPLE, DIRECT_SAMPLE, EXACT_EXT, RAGGED_EXT,  # noqa: E402
+                            EXACT_SHAPE, RAGGED_SHAPE, NARROW_SHAPE, RAGGED_BIG, ODD_SHAPE, BENCH_CONFIGS,
+                            SKINNY_CONFIGS, sample_configs)
+from tests.variants import some_configs as _some_configs  # noqa: E402
 
 
 def _sweep(space, indices, shape, alpha, beta, layout, seed, dist="uniform"):
@@ -67,79 +41,61 @@ def test_small_space_all_16_configs_at_256_cubed():
 
 
 def test_full_space_sample_exact_tiles():
-    _sweep(b.SPACE_FULL, gu.sample_configs(**FULL_SAMPLE), EXACT_SHAPE, 2.0, 0.5, 0, seed=21)
+    _sweep(b.SPACE_FULL, sample_configs(**FULL_SAMPLE), EXACT_SHAPE, 2.0, 0.5, 0, seed=21)
 
 
 def test_full_space_sample_ragged():
-    _sweep(b.SPACE_FULL, gu.sample_configs(**FULL_SAMPLE), RAGGED_SHAPE, 1.0, 1.0, 0, seed=22)
+    _sweep(b.SPACE_FULL, sample_configs(**FULL_SAMPLE), RAGGED_SHAPE, 1.0, 1.0, 0, seed=22)
 
 
 def test_mfma_space_sample_exact_tiles():
-    _sweep(b.SPACE_MFMA, gu.sample_configs(**MFMA_SAMPLE), EXACT_SHAPE, 1.0, 0.0, 0, seed=23,
+    _sweep(b.SPACE_MFMA, sample_configs(**MFMA_SAMPLE), EXACT_SHAPE, 1.0, 0.0, 0, seed=23,
            dist="normal")
 
 
 def test_mfma_space_sample_ragged():
-    _sweep(b.SPACE_MFMA, gu.sample_configs(**MFMA_SAMPLE), RAGGED_BIG, -1.5, 0.25, 0, seed=24)
+    _sweep(b.SPACE_MFMA, sample_configs(**MFMA_SAMPLE), RAGGED_BIG, -1.5, 0.25, 0, seed=24)
 
 
 def test_ext_space_sample_exact_tiles():
-    _sweep(b.SPACE_EXT, gu.sample_configs(**EXT_SAMPLE), EXACT_EXT, 1.5, -0.5, 0, seed=25)
+    _sweep(b.SPACE_EXT, sample_configs(**EXT_SAMPLE), EXACT_EXT, 1.5, -0.5, 0, seed=25)
 
 
 def test_ext_space_sample_ragged():
-    _sweep(b.SPACE_EXT, gu.sample_configs(**EXT_SAMPLE), RAGGED_EXT, 1.0, 1.0, 0, seed=26,
+    _sweep(b.SPACE_EXT, sample_configs(**EXT_SAMPLE), RAGGED_EXT, 1.0, 1.0, 0, seed=26,
            dist="normal")
 
 
 def test_direct_space_sample_exact_tiles():
-    _sweep(b.SPACE_DIRECT, gu.sample_configs(**DIRECT_SAMPLE), EXACT_EXT, 1.0, 0.0, 0, seed=27,
+    _sweep(b.SPACE_DIRECT, sample_configs(**DIRECT_SAMPLE), EXACT_EXT, 1.0, 0.0, 0, seed=27,
            dist="normal")
 
 
 def test_direct_space_sample_ragged():
-    idx = gu.sample_configs(**DIRECT_SAMPLE)
+    idx = sample_configs(**DIRECT_SAMPLE)
     _sweep(b.SPACE_DIRECT, idx, RAGGED_EXT, 2.0, 0.5, 0, seed=28)
     # odd sizes: the stored rows end inside a 16-byte vector, so the loads are narrowed
-    _sweep(b.SPACE_DIRECT, idx[::4], (203, 137, 67), 1.0, 1.0, 0, seed=29)
+    _sweep(b.SPACE_DIRECT, idx[::4], ODD_SHAPE, 1.0, 1.0, 0, seed=29)
 
 
 @pytest.mark.parametrize("layout", [1, 2, 3])
 def test_direct_space_transposed_storage(layout):
-    idx = gu.sample_configs(b.SPACE_DIRECT, 24, seed=300 + layout)
+    idx = sample_configs(b.SPACE_DIRECT, 24, seed=300 + layout)
     _sweep(b.SPACE_DIRECT, idx, EXACT_EXT, 1.0, 0.0, layout, seed=80 + layout)
     _sweep(b.SPACE_DIRECT, idx, RAGGED_EXT, -1.0, 0.5, layout, seed=90 + layout)
 
 
 @pytest.mark.parametrize("layout", [1, 2, 3])
 def test_ext_space_transposed_storage(layout):
-    idx = gu.sample_configs(b.SPACE_EXT, 24, seed=200 + layout)
+    idx = sample_configs(b.SPACE_EXT, 24, seed=200 + layout)
     _sweep(b.SPACE_EXT, idx, RAGGED_EXT, 0.75, 0.0, layout, seed=70 + layout)
 
 
 @pytest.mark.parametrize("layout", [1, 2, 3])
 def test_transposed_storage(layout):
-    idx = gu.sample_configs(b.SPACE_FULL, 40, seed=100 + layout)
+    idx = sample_configs(b.SPACE_FULL, 40, seed=100 + layout)
     _sweep(b.SPACE_FULL, idx, EXACT_SHAPE, 1.0, 0.0, layout, seed=30 + layout)
     _sweep(b.SPACE_FULL, idx, RAGGED_SHAPE, 0.5, 2.0, layout, seed=40 + layout)
-
-
-def _some_configs():
-    """A vector-ALU variant, a 32x32x2 MFMA variant, a 16x16x4 MFMA variant, and three
-    split-K variants (vector ALU, MFMA with a 96-wide tile, MFMA split 16 ways), and three
-    variants fed by LDS-direct loads (three LDS buffers; four buffers with split K; vector ALU
-    with A direct and B through registers)."""
-    return [
-        b.make_config(64, 64, 16, 8, 8, 4, 4, 1, 1, 1, 8, 0, 0),
-        b.make_config(128, 128, 16, 16, 16, 4, 4, 1, 1, 1, 8, 1, 1),
-        b.make_config(64, 64, 16, 16, 16, 2, 2, 1, 1, 0, 8, 2, 1),
-        b.make_config(64, 64, 16, 8, 8, 4, 4, 1, 1, 1, 8, 0, 0, 3),
-        b.make_config(96, 64, 16, 8, 16, 4, 4, 1, 1, 1, 8, 1, 1, 4),
-        b.make_config(32, 32, 8, 8, 8, 1, 1, 1, 1, 0, 2, 1, 0, 16),
-        b.make_config(128, 128, 16, 16, 16, 4, 4, 2, 2, 0, 8, 1, 1, 1, 3),
-        b.make_config(64, 64, 32, 8, 8, 4, 4, 2, 2, 0, 8, 2, 0, 2, 4),
-        b.make_config(64, 64, 16, 8, 8, 4, 4, 2, 1, 1, 8, 0, 0, 1, 2),
-    ]
 
 
 WHICH = list(range(9))
@@ -323,7 +279,7 @@ def test_reference_kernel_against_oracle():
 
 @pytest.mark.parametrize("which", [1, 4, 5, 7])
 def test_run_to_run_determinism(which):
-    """No atomics anywhere: split-K planes are added in index order."""
+    """No atomics anywhere: split-K planes are added in index order by the reduction kernel."""
     cfg = _some_configs()[which]
     A, B, C = synth.make_inputs(384, 256, 512, 0, seed=61)
     first = gu.run_gpu(cfg, A, B, C, 1.0, 0.0)
@@ -335,6 +291,9 @@ def test_run_to_run_determinism(which):
 # At 4096^3 the oracle cannot produce the whole matrix in test time, but every element is an
 # independent dot product: whole rows, whole columns, edge tiles and scattered elements are
 # computed one by one and compared under the same bound.
+
+_SAMPLED_REFERENCE = {}
+
 
 def _sampled_check(workload, cfg, entry="config", rows=64, cols=64, scattered=4096):
     import torch
@@ -348,22 +307,18 @@ def _sampled_check(workload, cfg, entry="config", rows=64, cols=64, scattered=40
         b.sgemm_tuned_on(None, w.M, w.N, w.K, w.alpha, dA, lda, dB, ldb, w.beta, dC, ldc, w.layout)
     torch.cuda.synchronize()
     got = dC.cpu().numpy()
-    r, c = synth.sample_positions(w.M, w.N, w.seed, rows=rows, cols=cols, scattered=scattered)
-    ref = orc.sgemm_sample(w.alpha, A, B, w.beta, C, r, c, w.layout)
+    key = (workload, rows, cols, scattered)
+    if key not in _SAMPLED_REFERENCE:   # the oracle's values depend on the workload only
+        r, c = synth.sample_positions(w.M, w.N, w.seed, rows=rows, cols=cols, scattered=scattered)
+        _SAMPLED_REFERENCE.clear()      # one workload's sample at a time is kept
+        _SAMPLED_REFERENCE[key] = (r, c, orc.sgemm_sample(w.alpha, A, B, w.beta, C, r, c, w.layout))
+    r, c, ref = _SAMPLED_REFERENCE[key]
     tol = orc.tolerance(w.K, np.max(np.abs(A)), np.max(np.abs(B)), ref)
     err = np.abs(got[r, c].astype(np.float64) - ref)
     assert np.all(err <= tol), (workload, cfg, float(np.max(err / tol)))
     # property that holds at any size: nothing non-finite, nothing left unwritten
     assert np.all(np.isfinite(got))
     return float(np.max(err / tol))
-
-
-BENCH_CONFIGS = [
-    b.make_config(256, 256, 32, 32, 16, 4, 4, 1, 1, 1, 8, 1, 1),
-    b.make_config(256, 256, 32, 16, 16, 4, 4, 2, 2, 0, 8, 1, 1, 1, 2),
-    b.make_config(128, 128, 16, 16, 16, 4, 4, 1, 1, 1, 8, 1, 1),
-    b.make_config(64, 64, 16, 8, 8, 4, 4, 1, 1, 1, 8, 0, 1),
-]
 
 
 @pytest.mark.parametrize("which", range(len(BENCH_CONFIGS)))
@@ -377,8 +332,8 @@ def test_dispatch_entry_point_at_headline_size():
 
 @pytest.mark.parametrize("workload", ["cfg5_128x4096x4096", "cfg5_4096x64x9216"])
 def test_deep_learning_shapes_a_transposed(workload):
-    _sampled_check(workload, b.make_config(64, 64, 16, 16, 16, 4, 4, 1, 1, 1, 8, 1, 0), rows=16, cols=16)
-    _sampled_check(workload, b.make_config(64, 64, 32, 16, 16, 4, 4, 1, 1, 1, 8, 1, 0, 8), rows=16, cols=16)
+    for cfg in SKINNY_CONFIGS:
+        _sampled_check(workload, cfg, rows=16, cols=16)
     _sampled_check(workload, None, entry="tuned", rows=16, cols=16)
 
 
@@ -392,6 +347,34 @@ def test_non_tile_multiple_sizes_full_compare(workload):
         gu.check_against_oracle(got, A, B, C, w.alpha, w.beta, w.layout, ref, what=f"{workload} {cfg}")
     got = gu.run_gpu(None, A, B, C, w.alpha, w.beta, w.layout, entry="tuned")
     gu.check_against_oracle(got, A, B, C, w.alpha, w.beta, w.layout, ref, what=f"{workload} tuned")
+
+
+def test_paper_workload_2048_cubed_full_compare():
+    """Benchmark configuration 2, the paper's own search-strategy workload (2048^3, alpha = 2,
+    beta = 0.5; first equation of the matrix-multiplication case study): every element of C
+    against the oracle, for the committed winner run explicitly and through the dispatch."""
+    w = synth.WORKLOADS["cfg2_2048"]
+    A, B, C = synth.make_workload(w)
+    ref = orc.sgemm(w.alpha, A, B, w.beta, C, w.layout)
+    _restore_cache()
+    winner = b.sgemm_config_get(w.M, w.N, w.K, w.layout)
+    assert winner is not None
+    for cfg, entry in [(winner, "config"), (None, "tuned"), (BENCH_CONFIGS[0], "config")]:
+        got = gu.run_gpu(cfg, A, B, C, w.alpha, w.beta, w.layout, entry=entry)
+        gu.check_against_oracle(got, A, B, C, w.alpha, w.beta, w.layout, ref, what=f"cfg2_2048 {entry} {cfg}")
+
+
+@pytest.mark.parametrize("workload,rows,cols", [("cfg3_3000", 64, 64), ("cfg4_8192", 64, 64)])
+def test_largest_benchmark_sizes_sampled(workload, rows, cols):
+    """3000^3 (192 x 192 tiles with a ragged edge on every side, alpha = beta = 1) and 8192^3:
+    whole rows, whole columns, the edge tiles and scattered elements against the oracle, for the
+    committed winner run explicitly and through the dispatch."""
+    w = synth.WORKLOADS[workload]
+    _restore_cache()
+    winner = b.sgemm_config_get(w.M, w.N, w.K, w.layout)
+    assert winner is not None
+    _sampled_check(workload, winner, rows=rows, cols=cols)
+    _sampled_check(workload, None, entry="tuned", rows=rows, cols=cols)
 
 
 # ---- the tuner and the dispatch entry points on the device ---------------------------------
@@ -442,6 +425,39 @@ def test_tune_ex_full_search_of_the_small_space(tmp_path):
         torch.cuda.synchronize()
         gu.check_against_oracle(dC.cpu().numpy(), A, B, C, w.alpha, w.beta, w.layout)
     finally:
+        _restore_cache()
+
+
+def test_verification_catches_a_variant_that_leaves_a_tile_unwritten(tmp_path, monkeypatch):
+    """The paper's verification of every tested configuration ("Advanced usage") must not be
+    fooled by stale output: with beta = 0, C still holds the previous candidate's correct result
+    when the next candidate runs.  Variants built with a planted bug (one workgroup returns
+    without writing its tile) are all rejected, in a search that follows an honest one on the
+    same C."""
+    import json
+    w, (A, B, C), dA, dB, dC, dC0 = _device_operands("cfg1_256")
+    assert w.beta == 0.0
+    log = tmp_path / "evals.jsonl"
+    opts = b.tune_opts()
+    opts.space = b.SPACE_SMALL
+    opts.A, opts.B, opts.C, opts.C0 = dA.data_ptr(), dB.data_ptr(), dC.data_ptr(), dC0.data_ptr()
+    opts.lda, opts.ldb, opts.ldc = w.K, w.N, w.N
+    opts.reps, opts.warmup_ms = 3, -1.0
+    opts.log_path = str(log).encode()
+    b.sgemm_cache_clear()
+    try:
+        evals, res = b.tune_ex(w.M, w.N, w.K, w.layout, w.alpha, w.beta, b.STRATEGY_FULL, 0, 0, opts)
+        assert evals == 16 and res.failed == 0          # C now holds a correct result
+        gu.check_against_oracle(dC.cpu().numpy(), A, B, C, w.alpha, w.beta, w.layout)
+        log.write_text("")
+        monkeypatch.setenv("SGEMM_TUNED_EXTRA_DEFINES", "-DPLANT_SKIP_TILE=1")
+        with pytest.raises(b.SgemmError) as e:
+            b.tune_ex(w.M, w.N, w.K, w.layout, w.alpha, w.beta, b.STRATEGY_FULL, 0, 0, opts)
+        assert e.value.status == b.E_NOCONFIG
+        rows = [json.loads(line) for line in log.read_text().splitlines()]
+        assert len(rows) == 16 and all(r["status"] == "verify" for r in rows), [r["status"] for r in rows]
+    finally:
+        monkeypatch.delenv("SGEMM_TUNED_EXTRA_DEFINES", raising=False)
         _restore_cache()
 
 
