@@ -342,12 +342,8 @@ int launch_planned(hipStream_t s, const LoadedKernel &k, int tiles_m, int tiles_
     const long long wgs = (long long)tiles_m * tiles_n;
     if (wgs > 0x7fffffffll) return SGEMM_E_BADARG;
     void *args[] = {&M, &N, &K, &alpha, &A, &lda, &B, &ldb, &beta, &C, &ldc, &tiles_m, &tiles_n, &k_chunk, &planes};
-    static const unsigned dyn_lds = [] { // experiment: unused dynamic LDS caps the workgroups per CU
-        const char *e = std::getenv("SGEMM_TUNED_EXPERIMENT_DYN_LDS");
-        return e ? (unsigned)std::atoi(e) : 0u;
-    }();
     const hipError_t e = hipModuleLaunchKernel(k.fn, (unsigned)wgs, (unsigned)parts, 1, (unsigned)k.threads, 1, 1,
-                                               dyn_lds, s, args, nullptr);
+                                               0, s, args, nullptr);
     if (e != hipSuccess) {
         set_error(std::string("hipModuleLaunchKernel: ") + hipGetErrorString(e));
         return SGEMM_E_LAUNCH;
