@@ -70,21 +70,59 @@ def worst_lds_bytes(cfg):
     return max(lds_bytes(cfg, layout) for layout in range(4))
 
 
+# Register file of a gfx950 SIMD: 512 registers per lane (architected VGPRs and accumulation
+# VGPRs together), shared by the waves resident on the SIMD; a wave addresses at most 256 of
+# each kind.  A workgroup of T threads is T/64 waves on 4 SIMDs, so the compiler may give each
+# wave no more than 512 / ceil(T/256) registers (its launch bound).
+REGISTERS_PER_LANE = 512
+MAX_ACCUMULATION_REGISTERS = 256
+
+
+def register_budget(threads):
+    waves_per_simd = -(-threads // 256)
+    return REGISTERS_PER_LANE // waves_per_simd
+
+
 def register_estimate(cfg):
-    MWG, NWG, KWG, MDIMC, NDIMC, _, _, SA, SB, _, KWI, MFMA = cfg[:12]
+    """(accumulators, everything else) a lane needs.  Everything else: two blocks of operand
+    fragments (the block being multiplied and the one fetched ahead), the registers that stage
+    the next slab on its way from global memory to LDS, two address registers per global load
+    instruction of a slab, and 24 for loop state, tile origin and the epilogue.  The last two
+    terms are fitted to what the compiler reports ("register model")."""
+    MWG, NWG, KWG, MDIMC, NDIMC, VWM, VWN, SA, SB, _, KWI, MFMA = cfg[:12]
     threads = MDIMC * NDIMC
     MWI, NWI = MWG // MDIMC, NWG // NDIMC
-    regs = MWI * NWI + 24                       # accumulators + addressing
+    acc = MWI * NWI
     if MFMA:
         tile, depth = (32, 2) if MFMA == 1 else (16, 4)
-        regs += (8 * MWI // tile + 8 * NWI // tile) * (KWI // depth)   # one fragment block
+        fragments = (8 * MWI // tile + 8 * NWI // tile) * (KWI // depth)
     else:
-        regs += MWI + NWI
-    if SA == 1:
-        regs += MWG * KWG // threads            # global -> LDS staging registers
-    if SB == 1:
-        regs += NWG * KWG // threads
-    return regs
+        fragments = MWI + NWI
+    staging = loads = 0
+    if SA:
+        loads += MWG * KWG // (threads * VWM)
+        if SA == 1:
+            staging += MWG * KWG // threads
+    if SB:
+        loads += NWG * KWG // (threads * VWN)
+        if SB == 1:
+            staging += NWG * KWG // threads
+    return acc, 2 * fragments + staging + 2 * loads + 24
+
+
+def registers_fit(cfg):
+    MDIMC, NDIMC, MFMA = cfg[3], cfg[4], cfg[11]
+    acc, other = register_estimate(cfg)
+    budget = register_budget(MDIMC * NDIMC)
+    if not MFMA:
+        budget = min(budget, 256)           # no accumulation registers without the matrix cores
+    if acc + other > budget:
+        return False
+    # 16x16x4 tiles whose accumulators would take all 256 accumulation registers: the compiler
+    # spills them (64 tiles of 4 registers each; measured on every such variant that was built)
+    if MFMA == 2 and acc >= MAX_ACCUMULATION_REGISTERS:
+        return False
+    return True
 
 
 def valid(cfg):
@@ -147,7 +185,7 @@ def valid(cfg):
         tile, depth = (32, 2) if MFMA == 1 else (16, 4)
         if (8 * MWI) % tile or (8 * NWI) % tile or KWI % depth or MWI * NWI > 256:
             return False
-    if register_estimate(cfg) > (512 if MFMA else 256):
+    if not registers_fit(cfg):
         return False
     if worst_lds_bytes(cfg) > LDS_LIMIT:
         return False

@@ -40,13 +40,21 @@ def precompile(space=0, layouts=(0,), edges=(0,), jobs=8, indices=None, verbose=
         for layout in layouts:
             for edge in edges:
                 if indices is None:
-                    tasks = [(space, layout, edge, j, n, jobs * 8) for j in range(jobs * 8)]
-                    res = pool.map(_work, tasks)
+                    indices_now = range(n)
                 else:
+                    indices_now = indices
+                # small strided chunks, so that progress can be reported while the pool works
+                chunks = max(jobs * 8, len(indices_now) // 16)
+                tasks = [(space, layout, edge, j, len(indices_now), chunks) for j in range(chunks)]
+                if indices is not None:
                     tasks = [(space, layout, edge, i, i + 1, 1) for i in indices]
-                    res = pool.map(_work, tasks, chunksize=max(1, len(tasks) // (jobs * 4)))
-                total_new += sum(r[0] for r in res)
-                total_fail += sum(r[1] for r in res)
+                last = time.time()
+                for done, r in enumerate(pool.imap_unordered(_work, tasks), 1):
+                    total_new += r[0]
+                    total_fail += r[1]
+                    if verbose and time.time() - last > 20:
+                        last = time.time()
+                        print(f"  {done}/{len(tasks)} chunks, compiled {total_new}, {time.time() - t0:.0f} s", flush=True)
                 if verbose:
                     print(f"space {space} layout {layout} edge {edge}: compiled so far "
                           f"{total_new}, failed {total_fail}, {time.time() - t0:.0f} s", flush=True)

@@ -1,5 +1,7 @@
 """The enumerated search space of the library against an independent enumeration
 (oracle/space_oracle.py), plus brute-force checks of the constraints themselves."""
+import os
+
 import numpy as np
 import pytest
 
@@ -117,3 +119,102 @@ def test_predicted_lds_size_matches_the_compiled_variants(tmp_path):
             assert checked >= 2
     finally:
         b.sgemm_kernel_cache_dir(os.path.join(os.path.dirname(b.LIB_PATH), "kcache"))
+
+
+# ---- pins of the device-limit rules that no closed form fixes: the compiler decides ---------
+# (paper, "Advanced usage": configurations that exceed a device limit are pruned.  The register
+# file and the counter of outstanding loads are such limits; what a variant needs of them is
+# known exactly only after compilation, so the oracle's rules are held to the compiler here.)
+
+KERNEL_SOURCE = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))),
+                             "paper_1703_06503_amd", "csrc", "sgemm_kernel.hip.inc")
+MACRO_NAMES = ("MWG", "NWG", "KWG", "MDIMC", "NDIMC", "VWM", "VWN", "SA", "SB", "PAD", "KWI", "MFMA", "GRP")
+
+
+def compile_raw(cfg, layout=0, edge=0):
+    """Compile the kernel family's source for ANY parameter values, valid or not, through the
+    generic tuner (which knows nothing of the GEMM constraints); returns the compiler's report
+    or raises SgemmError with the compiler's message."""
+    text = (f"#define TRA {layout & 1}\n#define TRB {layout >> 1}\n#define EDGE {edge}\n#define NS {cfg[14]}\n"
+            + open(KERNEL_SOURCE).read())
+    t = b.ktuner_create(text, "sgemm_variant", (64, 1, 1), (64, 1, 1))
+    try:
+        for name, value in zip(MACRO_NAMES, cfg):
+            b.ktuner_add_parameter(t, name, [int(value)])
+        assert b.ktuner_space_size(t) == 1
+        return b.ktuner_compile(t, 0)
+    finally:
+        b.ktuner_destroy(t)
+
+
+def test_register_model_against_the_compiler():
+    """A seeded sample of what the oracle admits, compiled for gfx950 (no GPU needed): the
+    compiler never exceeds the register budget the oracle derives from the workgroup size, it
+    keeps at least the accumulators the oracle counts, and (almost) nothing admitted spills -
+    also in the riskiest corner, where the accumulators take half of the budget."""
+    rng = np.random.default_rng(77)
+    sample = []
+    for preset in (so.SPACE_FULL, so.SPACE_MFMA, so.SPACE_EXT, so.SPACE_DIRECT):
+        space = so.enumerate_space(preset) if preset in (so.SPACE_FULL, so.SPACE_MFMA) else None
+        if space is None:      # the two large presets: draw from the raw product, keep the valid
+            lists = so.VALUES[preset]
+            space = []
+            while len(space) < 400:
+                cfg = tuple(int(v[rng.integers(len(v))]) for v in lists)
+                if so.valid(cfg):
+                    space.append(cfg)
+        picks = [space[int(i)] for i in rng.choice(len(space), size=10, replace=False)]
+        corner = [c for c in space if c[11] and 2 * so.register_estimate(c)[0] == so.register_budget(c[3] * c[4])]
+        picks += [corner[int(i)] for i in rng.choice(len(corner), size=min(4, len(corner)), replace=False)]
+        sample += picks
+    spilled = []
+    for cfg in sample:
+        threads = cfg[3] * cfg[4]
+        acc, other = so.register_estimate(cfg)
+        info = b.sgemm_kernel_compile(b.make_config(*cfg), 0, 0)
+        # registers reported: architected + accumulation together (unified file)
+        assert info.vgprs <= so.register_budget(threads), (cfg, info.vgprs)
+        assert info.vgprs >= acc, (cfg, info.vgprs, acc)
+        if info.scratch_bytes > 0:
+            spilled.append(cfg)
+    assert len(sample) >= 50
+    assert len(spilled) <= 2, spilled           # under 4 % of the sample, corner cases included
+
+
+def test_what_the_register_model_rejects_does_spill():
+    """Three configurations that only the register rules reject (every divisibility and LDS
+    rule holds), one per rule: they compile, and the compiler reports spills."""
+    cases = [
+        # 16x16x4 tiles with all 256 accumulation registers taken by accumulators
+        (256, 256, 16, 16, 16, 4, 4, 1, 1, 1, 8, 2, 0, 1, 2),
+        # 1024 threads leave 128 registers per lane: 64 accumulators and the rest do not fit
+        (256, 256, 16, 32, 32, 4, 4, 1, 1, 1, 8, 1, 0, 1, 2),
+        # one wave, 256 accumulators, and 160 staging registers on top
+        (64, 256, 32, 8, 8, 4, 4, 1, 1, 1, 8, 1, 0, 1, 2),
+    ]
+    for cfg in cases:
+        assert not so.registers_fit(cfg) and not so.valid(cfg), cfg
+        relaxed = so.registers_fit
+        so.registers_fit = lambda c: True
+        try:
+            assert so.valid(cfg), cfg           # nothing but the register rules is in the way
+        finally:
+            so.registers_fit = relaxed
+        assert b.sgemm_config_check(b.make_config(*cfg)) == b.E_INVALID
+        info = compile_raw(cfg)
+        assert info.scratch_bytes > 0, (cfg, info.vgprs)
+
+
+def test_loads_in_flight_rule_is_what_the_kernel_itself_asserts():
+    """More than two LDS buffers keep the loads of NS - 2 slabs in flight behind the slab that
+    is waited for, and the wait is a 6-bit count: the kernel source refuses to compile beyond
+    63.  The oracle's rule draws the same line: 2 x 32 loads is rejected, 1 x 32 is admitted."""
+    four = (64, 64, 64, 16, 16, 1, 1, 2, 2, 0, 8, 1, 0, 1, 4)      # 32 loads per slab and thread
+    three = four[:14] + (3,)
+    assert so.valid(three) and not so.valid(four)
+    assert b.sgemm_config_check(b.make_config(*three)) == 0
+    assert b.sgemm_config_check(b.make_config(*four)) == b.E_INVALID
+    assert compile_raw(three).scratch_bytes == 0
+    with pytest.raises(b.SgemmError) as e:
+        compile_raw(four)
+    assert "too many LDS-direct loads in flight" in str(e.value)
