@@ -1,5 +1,6 @@
 #include "space.h"
 
+#include <algorithm>
 #include <cstdlib>
 #include <mutex>
 
@@ -51,22 +52,28 @@ static bool is_tile_edge(int v, int lo, int hi) {
     return v % 3 == 0 && ((v / 3) & (v / 3 - 1)) == 0;
 }
 
-// Registers a lane needs at least: accumulators, one KWI block of operand fragments, the
-// global->LDS staging registers, and about 24 for addresses and loop state.
+// Registers a lane needs beside its accumulators: two KWI blocks of operand fragments (the one
+// being multiplied and the one fetched ahead), the global->LDS staging registers, two address
+// registers per global load instruction of a slab, and 24 for loop state and the epilogue.
 int estimated_registers(const sgemm_config &c) {
     const int nt = c.mdimc * c.ndimc;
     const int mwi = c.mwg / c.mdimc, nwi = c.nwg / c.ndimc;
-    int regs = mwi * nwi + 24;
+    int fragments;
     if (c.mfma) {
         const int mt = c.mfma == 1 ? 32 : 16, mk = c.mfma == 1 ? 2 : 4;
-        regs += ((8 * mwi) / mt + (8 * nwi) / mt) * (c.kwi / mk);
+        fragments = ((8 * mwi) / mt + (8 * nwi) / mt) * (c.kwi / mk);
     } else {
-        regs += mwi + nwi;
+        fragments = mwi + nwi;
     }
-    if (c.sa == 1) regs += c.mwg * c.kwg / nt;
-    if (c.sb == 1) regs += c.nwg * c.kwg / nt;
+    int regs = 2 * fragments + 24;
+    if (c.sa) regs += 2 * (c.mwg * c.kwg / (nt * c.vwm)) + (c.sa == 1 ? c.mwg * c.kwg / nt : 0);
+    if (c.sb) regs += 2 * (c.nwg * c.kwg / (nt * c.vwn)) + (c.sb == 1 ? c.nwg * c.kwg / nt : 0);
     return regs;
 }
+
+// 512 registers per lane of a SIMD (VGPRs and accumulation VGPRs together), shared by the
+// workgroup's waves on that SIMD: nt / 64 waves on 4 SIMDs.
+static int register_budget(int nt) { return 512 / ((nt + 255) / 256); }
 
 int direct_loads_per_slab(const sgemm_config &c) {
     const int nt = c.mdimc * c.ndimc;
@@ -126,8 +133,12 @@ const char *violates(const sgemm_config &c) {
         if (c.kwi % mk) return "KWI not a multiple of the MFMA depth";
         if (mwi * nwi > 256) return "accumulator tile too large";
     }
-    // device limits: 512 registers per lane (VGPR + AGPR), 160 KiB LDS per workgroup
-    if (estimated_registers(c) > (c.mfma ? 512 : 256)) return "register budget";
+    // device limits: the register file (without the matrix cores there are no accumulation
+    // registers, so 256 at most), 160 KiB LDS per workgroup
+    const int budget = c.mfma ? register_budget(nt) : std::min(register_budget(nt), 256);
+    if (mwi * nwi + estimated_registers(c) > budget) return "register budget";
+    // 16x16x4 tiles that would take all 256 accumulation registers: every such variant spills
+    if (c.mfma == 2 && mwi * nwi >= 256) return "accumulators leave no accumulation register free";
     if (lds_bytes(c) > kLdsLimitBytes) return "LDS capacity";
     return nullptr;
 }

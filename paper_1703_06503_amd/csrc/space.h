@@ -28,7 +28,7 @@ const char *dim_name(int d);
 // Derived quantities of one configuration.
 int lds_bytes(const sgemm_config &c);       // worst case over the four storage layouts
 int lds_bytes(const sgemm_config &c, int layout);
-int estimated_registers(const sgemm_config &c);
+int estimated_registers(const sgemm_config &c); // beside the accumulators
 int direct_loads_per_slab(const sgemm_config &c); // LDS-direct load instructions per thread
 
 // nullptr if c satisfies every constraint, else a short reason.
