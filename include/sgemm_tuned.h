@@ -310,7 +310,9 @@ long long sgemm_config_workspace_bytes(const sgemm_config *cfg, int M, int N, in
  * or $SGEMM_TUNED_CACHE_DIR). */
 int sgemm_kernel_cache_dir(const char *path);
 /* [host] Compile (or fetch from the cache) the variant for cfg/layout; edge = 1 builds the
- * bounds-guarded form.  cfg->sk > 1 selects the build that split-K launches use (one build
+ * bounds-guarded form.  cfg must satisfy every constraint but the register estimate (the build
+ * that sgemm_kernel_resolve() names may have narrower load vectors than the configuration it
+ * came from and then exceeds the estimate; it still has to be built).  cfg->sk > 1 selects the build that split-K launches use (one build
  * for every sk > 1: the split itself is a launch parameter).  Needs no GPU.  info may be null. */
 int sgemm_kernel_compile(const sgemm_config *cfg, int layout, int edge, sgemm_kernel_info *info);
 /* [host] Which build a call with cfg launches for these sizes and leading dimensions when the

@@ -272,11 +272,16 @@ def lib():
 
 
 class SgemmError(RuntimeError):
-    def __init__(self, status, what):
+    def __init__(self, status, what, message=None):
         self.status = status
-        detail = sgemm_last_error()
-        super().__init__(f"{what}: {sgemm_status_string(status)} ({status})"
-                         + (f": {detail}" if detail else ""))
+        self.what = what
+        if message is None:
+            detail = sgemm_last_error()
+            message = f"{what}: {sgemm_status_string(status)} ({status})" + (f": {detail}" if detail else "")
+        super().__init__(message)
+
+    def __reduce__(self):       # travels between processes (worker pools) with its text
+        return (SgemmError, (self.status, self.what, str(self)))
 
 
 def _check(status, what):

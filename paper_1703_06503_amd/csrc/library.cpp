@@ -108,7 +108,7 @@ int load_cache_file_locked(const char *path) {
                                     &p[6], &p[7], &p[8], &p[9], &p[10], &p[11], &p[12], &p[13], &p[14]);
         if (got < 18 || got > 20) continue;
         sgemm_config c = from_point(p);
-        if (violates(c) || M < 0 || N < 0 || K < 0 || layout < 0 || layout > 3) continue;
+        if (violates_structure(c) || M < 0 || N < 0 || K < 0 || layout < 0 || layout > 3) continue;
         g_tuned[ShapeKey{M, N, K, layout}] = Tuned{c, ms};
         ++added;
     }
@@ -402,7 +402,7 @@ int run_config(hipStream_t s, const sgemm_config &cfg, int M, int N, int K, floa
     const bool need_ab = (alpha != 0.0f);
     int rc = check_gemm_args(M, N, K, A, lda, B, ldb, C, ldc, layout, need_ab);
     if (rc != SGEMM_OK) return rc;
-    if (violates(cfg)) return SGEMM_E_INVALID;
+    if (violates_structure(cfg)) return SGEMM_E_INVALID;
     if (M == 0 || N == 0) return SGEMM_OK;
     if (K == 0 || alpha == 0.0f) {
         if (beta == 1.0f) return SGEMM_OK;
@@ -606,7 +606,7 @@ int sgemm_run_config_padded(void *hip_stream, const sgemm_config *cfg, int M, in
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     int rc = check_gemm_args(M, N, K, A, lda, B, ldb, C, ldc, layout, alpha != 0.0f);
     if (rc != SGEMM_OK) return rc;
-    if (violates(*cfg)) return SGEMM_E_INVALID;
+    if (violates_structure(*cfg)) return SGEMM_E_INVALID;
     const int Mp = (M + cfg->mwg - 1) / cfg->mwg * cfg->mwg;
     const int Np = (N + cfg->nwg - 1) / cfg->nwg * cfg->nwg;
     const int Kp = (K + cfg->kwg - 1) / cfg->kwg * cfg->kwg;
@@ -768,7 +768,7 @@ static_assert(sgemm_util::kScratchFloats * sizeof(float) == SGEMM_NOALLOC_SCRATC
 int sgemm_config_prefers_padding(const sgemm_config *cfg, int M, int N, int K, int lda, int ldb, int ldc,
                                  int layout, float beta) {
     if (!cfg || M < 0 || N < 0 || K < 0 || layout < 0 || layout > 3) return SGEMM_E_BADARG;
-    if (violates(*cfg)) return SGEMM_E_INVALID;
+    if (violates_structure(*cfg)) return SGEMM_E_INVALID;
     const float *aligned = reinterpret_cast<const float *>(uintptr_t{256});
     return prefers_padding(*cfg, M, N, K, aligned, lda, aligned, ldb, aligned, ldc, layout, 1.0f, beta) ? 1 : 0;
 }
@@ -952,7 +952,7 @@ int sgemm_config_lds_bytes(const sgemm_config *cfg) {
 long long sgemm_config_workspace_bytes(const sgemm_config *cfg, int M, int N, int K, int *parts,
                                        int *k_chunk) {
     if (!cfg || M < 0 || N < 0 || K < 0) return SGEMM_E_BADARG;
-    if (violates(*cfg)) return SGEMM_E_INVALID;
+    if (violates_structure(*cfg)) return SGEMM_E_INVALID;
     const SplitPlan plan = plan_split(*cfg, K);
     if (parts) *parts = plan.parts;
     if (k_chunk) *k_chunk = plan.k_chunk;
@@ -975,7 +975,7 @@ int sgemm_kernel_cache_dir(const char *path) {
 
 int sgemm_kernel_compile(const sgemm_config *cfg, int layout, int edge, sgemm_kernel_info *info) {
     if (!cfg || layout < 0 || layout > 3) return SGEMM_E_BADARG;
-    if (violates(*cfg)) return SGEMM_E_INVALID;
+    if (violates_structure(*cfg)) return SGEMM_E_INVALID;
     CodeObject co;
     std::string log;
     const int rc = get_code_object(VariantKey{*cfg, layout, edge ? 1 : 0, cfg->sk > 1 ? 1 : 0}, &co, &log);
@@ -987,7 +987,7 @@ int sgemm_kernel_compile(const sgemm_config *cfg, int layout, int edge, sgemm_ke
 int sgemm_kernel_resolve(const sgemm_config *cfg, int M, int N, int K, int lda, int ldb, int ldc,
                          int layout, sgemm_config *variant, int *edge) {
     if (!cfg || !variant || !edge || M <= 0 || N <= 0 || K <= 0 || layout < 0 || layout > 3) return SGEMM_E_BADARG;
-    if (violates(*cfg)) return SGEMM_E_INVALID;
+    if (violates_structure(*cfg)) return SGEMM_E_INVALID;
     const float *aligned = reinterpret_cast<const float *>(uintptr_t{256}); // stands for any aligned pointer
     const VariantKey key = resolve_variant(*cfg, M, N, K, aligned, lda, aligned, ldb, aligned, ldc, layout);
     *variant = key.cfg;
@@ -998,7 +998,7 @@ int sgemm_kernel_resolve(const sgemm_config *cfg, int M, int N, int K, int lda, 
 
 int sgemm_kernel_cache_path(const sgemm_config *cfg, int layout, int edge, char *buf, int cap) {
     if (!cfg || !buf || cap <= 0 || layout < 0 || layout > 3) return SGEMM_E_BADARG;
-    if (violates(*cfg)) return SGEMM_E_INVALID;
+    if (violates_structure(*cfg)) return SGEMM_E_INVALID;
     const std::string p = code_object_path(VariantKey{*cfg, layout, edge ? 1 : 0, cfg->sk > 1 ? 1 : 0});
     if ((int)p.size() + 1 > cap) return SGEMM_E_BADARG;
     std::memcpy(buf, p.c_str(), p.size() + 1);

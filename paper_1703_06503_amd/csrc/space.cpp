@@ -84,6 +84,19 @@ int direct_loads_per_slab(const sgemm_config &c) {
 }
 
 const char *violates(const sgemm_config &c) {
+    if (const char *why = violates_structure(c)) return why;
+    const int nt = c.mdimc * c.ndimc;
+    const int mwi = c.mwg / c.mdimc, nwi = c.nwg / c.ndimc;
+    // device limit: the register file (without the matrix cores there are no accumulation
+    // registers, so 256 at most)
+    const int budget = c.mfma ? register_budget(nt) : std::min(register_budget(nt), 256);
+    if (mwi * nwi + estimated_registers(c) > budget) return "register budget";
+    // 16x16x4 tiles that would take all 256 accumulation registers: every such variant spills
+    if (c.mfma == 2 && mwi * nwi >= 256) return "accumulators leave no accumulation register free";
+    return nullptr;
+}
+
+const char *violates_structure(const sgemm_config &c) {
     if (!is_tile_edge(c.mwg, 8, 512) || !is_tile_edge(c.nwg, 8, 512)) return "tile size";
     if (!is_pow2_between(c.kwg, 2, 128)) return "KWG";
     if (!is_pow2_between(c.mdimc, 1, 64) || !is_pow2_between(c.ndimc, 1, 64)) return "workgroup shape";
@@ -133,12 +146,7 @@ const char *violates(const sgemm_config &c) {
         if (c.kwi % mk) return "KWI not a multiple of the MFMA depth";
         if (mwi * nwi > 256) return "accumulator tile too large";
     }
-    // device limits: the register file (without the matrix cores there are no accumulation
-    // registers, so 256 at most), 160 KiB LDS per workgroup
-    const int budget = c.mfma ? register_budget(nt) : std::min(register_budget(nt), 256);
-    if (mwi * nwi + estimated_registers(c) > budget) return "register budget";
-    // 16x16x4 tiles that would take all 256 accumulation registers: every such variant spills
-    if (c.mfma == 2 && mwi * nwi >= 256) return "accumulators leave no accumulation register free";
+    // device limit: 160 KiB LDS per workgroup
     if (lds_bytes(c) > kLdsLimitBytes) return "LDS capacity";
     return nullptr;
 }

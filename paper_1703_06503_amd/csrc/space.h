@@ -33,6 +33,11 @@ int direct_loads_per_slab(const sgemm_config &c); // LDS-direct load instruction
 
 // nullptr if c satisfies every constraint, else a short reason.
 const char *violates(const sgemm_config &c);
+// The same without the register-budget rules: what a variant must satisfy to be built and
+// launched at all.  (A configuration of a search space passes violates(); the build a call
+// really launches may have narrower load vectors than the configuration, hence more load
+// instructions and a larger register estimate, and still has to run.)
+const char *violates_structure(const sgemm_config &c);
 
 struct Space {
     int preset = -1;

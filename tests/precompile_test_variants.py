@@ -84,7 +84,15 @@ def conv_tasks():
 
 
 def _compile(task):
-    """1 if the variant was compiled now, 0 if it was in the cache already."""
+    """1 if the variant was compiled now, 0 if it was in the cache already; a failure comes back
+    as text (an exception raised in a pool worker must not be left to the pool to carry)."""
+    try:
+        return _compile_task(task)
+    except Exception as e:      # noqa: BLE001
+        return f"{task}: {e}"
+
+
+def _compile_task(task):
     if task[0] == "gemm":
         _, cfg, layout, edge, extra = task
         if extra:
@@ -103,7 +111,11 @@ def main(jobs=None, verbose=True):
     jobs = jobs or min(8, os.cpu_count() or 1)
     tasks = sorted(set(gemm_tasks() + conv_tasks()))
     with mp.get_context("spawn").Pool(jobs) as pool:
-        new = sum(pool.map(_compile, tasks, chunksize=4))
+        results = pool.map(_compile, tasks, chunksize=4)
+    failures = [r for r in results if isinstance(r, str)]
+    if failures:
+        raise RuntimeError(f"{len(failures)} variants failed to compile, the first: {failures[0]}")
+    new = sum(results)
     if verbose:
         print(f"kernel cache: {len(tasks)} variants wanted, {new} compiled now", flush=True)
     return len(tasks), new
