@@ -7,7 +7,10 @@ strategies and search-space properties").  This file writes out, in plain Python
 lists of the library's five presets and every constraint of its GEMM kernel family, and
 enumerates the product in lexicographic order (first parameter slowest).
 
-Parameters, in order: MWG NWG KWG MDIMC NDIMC VWM VWN SA SB PAD KWI MFMA GRP SK NS.
+Parameters, in order: MWG NWG KWG MDIMC NDIMC VWM VWN SA SB PAD KWI MFMA GRP SK NS KSW.
+(KSW: the K slab of a workgroup is shared out among KSW groups of waves, each group holding a
+full set of accumulators for the whole tile; the groups' sums are added at the end.  The
+workgroup then has MDIMC * NDIMC * KSW threads.)
 
 parity unpinned: the paper's own count of 241 600 valid GEMM configurations cannot be
 reproduced, because its constraint list is not printed; the counts here are pinned only by
@@ -16,23 +19,27 @@ the independent re-derivation below and by brute-force checks in the tests.
 import itertools
 
 NAMES = ("MWG", "NWG", "KWG", "MDIMC", "NDIMC", "VWM", "VWN", "SA", "SB", "PAD", "KWI", "MFMA",
-         "GRP", "SK", "NS")
+         "GRP", "SK", "NS", "KSW")
 
 SPACE_FULL, SPACE_SMALL, SPACE_MFMA, SPACE_EXT, SPACE_DIRECT = 0, 1, 2, 3, 4
+SPACE_KSPLIT = 6        # (5 is the caller-defined space)
 
 VALUES = {
     SPACE_FULL: ([32, 64, 128, 256], [32, 64, 128, 256], [8, 16, 32], [8, 16], [8, 16], [1, 4],
-                 [1, 4], [0, 1], [0, 1], [0, 1], [2, 8], [0, 1], [0, 1], [1], [2]),
+                 [1, 4], [0, 1], [0, 1], [0, 1], [2, 8], [0, 1], [0, 1], [1], [2], [1]),
     SPACE_SMALL: ([32, 64], [32, 64], [8, 16], [8], [8], [1], [1], [0, 1], [0, 1], [0], [2], [0],
-                  [0], [1], [2]),
+                  [0], [1], [2], [1]),
     SPACE_MFMA: ([64, 128, 256], [64, 128, 256], [8, 16, 32], [8, 16, 32], [8, 16, 32],
-                 [1, 2, 4], [1, 2, 4], [1], [1], [0, 1], [2, 8], [1, 2], [0, 1], [1], [2]),
+                 [1, 2, 4], [1, 2, 4], [1], [1], [0, 1], [2, 8], [1, 2], [0, 1], [1], [2], [1]),
     SPACE_EXT: ([32, 64, 96, 128, 192, 256], [32, 64, 96, 128, 192, 256], [16, 32, 64],
                 [8, 16, 32], [8, 16, 32], [1, 2, 4], [1, 2, 4], [1], [1], [0, 1], [2, 8], [1, 2],
-                [0, 1], [1, 2, 3, 4, 6, 8, 12, 16], [2]),
+                [0, 1], [1, 2, 3, 4, 6, 8, 12, 16], [2], [1]),
     SPACE_DIRECT: ([32, 64, 96, 128, 192, 256], [32, 64, 96, 128, 192, 256], [16, 32, 64],
                    [8, 16, 32], [8, 16, 32], [1, 4], [1, 4], [2], [2], [0], [2, 8], [1, 2],
-                   [0, 1], [1, 2, 3, 4, 6, 8, 12, 16], [2, 3, 4]),
+                   [0, 1], [1, 2, 3, 4, 6, 8, 12, 16], [2, 3, 4], [1]),
+    # matrix-core variants whose waves share out the K slab: small tiles, 2 or 4 wave groups
+    SPACE_KSPLIT: ([32, 64, 96, 128], [32, 64, 96, 128], [32, 64], [8, 16], [8, 16], [4], [4], [1],
+                   [1], [0, 1], [2, 8], [1, 2], [0, 1], [1, 2, 4], [2], [2, 4]),
 }
 
 LDS_LIMIT = 160 * 1024          # bytes per workgroup on gfx950
@@ -56,6 +63,7 @@ def lds_bytes(cfg, layout):
     LDS-direct loads, SA/SB = 2, cannot be padded)."""
     MWG, NWG, KWG, _, _, _, _, SA, SB, PAD = cfg[:10]
     NS = cfg[14] if len(cfg) > 14 else 2
+    KSW = cfg[15] if len(cfg) > 15 else 1
     pad_a = 4 if PAD and SA == 1 else 0
     pad_b = 4 if PAD and SB == 1 else 0
     floats = 0
@@ -63,7 +71,12 @@ def lds_bytes(cfg, layout):
         floats += KWG * (MWG + pad_a) if layout & 1 else MWG * (KWG + pad_a)
     if SB:
         floats += NWG * (KWG + pad_b) if layout & 2 else KWG * (NWG + pad_b)
-    return NS * 4 * floats
+    floats *= NS
+    if KSW > 1:
+        # the wave groups hand their sums over through LDS, one tile of C at a time, in the
+        # memory of the tile buffers: the allocation is the larger of the two
+        floats = max(floats, MWG * NWG)
+    return 4 * floats
 
 
 def worst_lds_bytes(cfg):
@@ -90,7 +103,7 @@ def register_estimate(cfg):
     instruction of a slab, and 24 for loop state, tile origin and the epilogue.  The last two
     terms are fitted to what the compiler reports ("register model")."""
     MWG, NWG, KWG, MDIMC, NDIMC, VWM, VWN, SA, SB, _, KWI, MFMA = cfg[:12]
-    threads = MDIMC * NDIMC
+    threads = MDIMC * NDIMC * (cfg[15] if len(cfg) > 15 else 1)
     MWI, NWI = MWG // MDIMC, NWG // NDIMC
     acc = MWI * NWI
     if MFMA:
@@ -113,7 +126,7 @@ def register_estimate(cfg):
 def registers_fit(cfg):
     MDIMC, NDIMC, MFMA = cfg[3], cfg[4], cfg[11]
     acc, other = register_estimate(cfg)
-    budget = register_budget(MDIMC * NDIMC)
+    budget = register_budget(MDIMC * NDIMC * (cfg[15] if len(cfg) > 15 else 1))
     if not MFMA:
         budget = min(budget, 256)           # no accumulation registers without the matrix cores
     if acc + other > budget:
@@ -129,6 +142,9 @@ def valid(cfg):
     MWG, NWG, KWG, MDIMC, NDIMC, VWM, VWN, SA, SB, PAD, KWI, MFMA, GRP = cfg[:13]
     SK = cfg[13] if len(cfg) > 13 else 1
     NS = cfg[14] if len(cfg) > 14 else 2
+    KSW = cfg[15] if len(cfg) > 15 else 1
+    if KSW not in (1, 2, 4) or (KSW > 1 and not MFMA):      # only the matrix-core schedule shares K out
+        return False
     if not (tile_edge_ok(MWG) and tile_edge_ok(NWG)):
         return False
     if not (_pow2(KWG) and 2 <= KWG <= 128 and _pow2(MDIMC) and _pow2(NDIMC)
@@ -140,13 +156,13 @@ def valid(cfg):
         return False
     if SA not in (0, 1, 2) or SB not in (0, 1, 2) or NS not in (2, 3, 4):
         return False
-    threads = MDIMC * NDIMC
-    if threads % 64 or threads > MAX_THREADS:           # whole wavefronts, device limit
+    threads = MDIMC * NDIMC * KSW
+    if (MDIMC * NDIMC) % 64 or threads > MAX_THREADS:   # whole wavefronts, device limit
         return False
     if MWG % MDIMC or NWG % NDIMC:                      # integer work per thread
         return False
     MWI, NWI = MWG // MDIMC, NWG // NDIMC
-    if KWG % KWI:
+    if KWG % (KWI * KSW):                               # whole KWI blocks for every wave group
         return False
     if SA:
         if MWG % VWM or KWG % VWM or (MWG * KWG) % (threads * VWM):
@@ -162,9 +178,9 @@ def valid(cfg):
         return False
     loads = 0                                           # LDS-direct loads per thread and slab
     if SA == 2:
-        loads += MWG * KWG // (MDIMC * NDIMC * VWM)
+        loads += MWG * KWG // (threads * VWM)
     if SB == 2:
-        loads += NWG * KWG // (MDIMC * NDIMC * VWN)
+        loads += NWG * KWG // (threads * VWN)
     if loads > MAX_LOADS_IN_FLIGHT:                     # one slab's loads must fit the counter
         return False
     if NS > 2:
