@@ -68,6 +68,9 @@ extern "C" {
                                split K (sk up to 16): for sizes that powers of two tile badly
                                and for shapes with few tiles and a long K */
 
+#define SGEMM_SPACE_KSPLIT 6 /* matrix-core variants with small tiles (32 to 128) whose waves share
+                               out the K slab (ksw 2 or 4), with split K 1, 2, 4: for problems too
+                               small to fill the chip with large tiles */
 #define SGEMM_SPACE_CUSTOM 5 /* value lists given by the caller: sgemm_space_define_custom() */
 
 /* One point of the parameter space.  Names follow the paper's GEMM parameters (list in
@@ -75,11 +78,11 @@ extern "C" {
  * Mwg/Nwg/Kwg, the workgroup shape MdimC x NdimC (so each thread owns Mwi = Mwg/MdimC by
  * Nwi = Nwg/NdimC accumulators), the vector widths of the off-chip loads, local-memory
  * staging per operand, and the unroll factor Kwi of the Kwg loop.  `pad`, `mfma`, `grp`,
- * `sk` and `ns` are gfx950 additions.  All fields are plain ints so the struct is an int[16]. */
+ * `sk`, `ns` and `ksw` are gfx950 additions.  All fields are plain ints so the struct is an int[16]. */
 typedef struct sgemm_config {
     int mwg, nwg, kwg; /* workgroup macro-tile of C (mwg x nwg: each 2^a or 3*2^a) and K slab
                           per step (power of two)                                          */
-    int mdimc, ndimc;  /* threads per workgroup = mdimc * ndimc (multiple of 64)         */
+    int mdimc, ndimc;  /* threads per workgroup = mdimc * ndimc (multiple of 64), times ksw */
     int vwm;           /* floats per global load of A (1, 2, 4)                          */
     int vwn;           /* floats per global load of B and per store of C (1, 2, 4)       */
     int sa, sb;        /* how the A / B tile reaches the arithmetic: 0 = operands read straight
@@ -100,7 +103,10 @@ typedef struct sgemm_config {
     int ns;            /* LDS buffers per staged tile: 2 (also meant by 0), 3 or 4; more than 2
                           needs every staged operand to use LDS-direct loads, which then
                           run ns - 1 K slabs ahead of the arithmetic                       */
-    int reserved[1];   /* must be 0                                                        */
+    int ksw;           /* matrix-core variants: the workgroup's waves form ksw groups (1, also
+                          meant by 0; 2; 4); each group multiplies 1/ksw of every K slab into
+                          accumulators of its own for the whole tile, and the groups' sums are
+                          added through LDS in group order.  Threads = mdimc * ndimc * ksw.      */
 } sgemm_config;
 
 /* What the generator knows about one compiled variant. */
@@ -279,7 +285,7 @@ int tune_replay(int space, const float *ms_table, int table_len, int strategy, i
  * kernel family ("CLTune: an auto-tuner for OpenCL kernels"): `spec` is HOST text of the form
  * "MWG=64,128 NWG=128 KWG=32,64 SK=4,8" - parameter names as in sgemm_config (upper case),
  * separated by blanks or ';'.  A parameter that is not named keeps one value (MWG=NWG=128 KWG=32
- * MDIMC=NDIMC=16 VWM=VWN=4 SA=SB=1 PAD=1 KWI=8 MFMA=1 GRP=0 SK=1 NS=2).  The product is pruned by
+ * MDIMC=NDIMC=16 VWM=VWN=4 SA=SB=1 PAD=1 KWI=8 MFMA=1 GRP=0 SK=1 NS=2 KSW=1).  The product is pruned by
  * the kernel family's constraints like every preset.  Returns the number of valid
  * configurations (>= 0) or SGEMM_E_BADARG.  A process that never calls this reads the
  * definition from $SGEMM_TUNED_CUSTOM_SPACE on first use.  Redefining the space while a search

@@ -15,15 +15,15 @@ E_BADARG, E_NOCONFIG, E_COMPILE, E_LAUNCH, E_VERIFY = -1, -2, -3, -4, -5
 E_INVALID, E_IO, E_NODEVICE, E_RESOURCE, E_NOTREADY = -6, -7, -8, -9, -10
 LAYOUT_A_TRANSPOSED, LAYOUT_B_TRANSPOSED = 1, 2
 STRATEGY_FULL, STRATEGY_RANDOM, STRATEGY_ANNEALING, STRATEGY_PSO = 0, 1, 2, 3
-SPACE_FULL, SPACE_SMALL, SPACE_MFMA, SPACE_EXT, SPACE_DIRECT, SPACE_CUSTOM = 0, 1, 2, 3, 4, 5
+SPACE_FULL, SPACE_SMALL, SPACE_MFMA, SPACE_EXT, SPACE_DIRECT, SPACE_CUSTOM, SPACE_KSPLIT = 0, 1, 2, 3, 4, 5, 6
 NOALLOC_SCRATCH_BYTES = 32 << 20
 
 CONFIG_FIELDS = ("mwg", "nwg", "kwg", "mdimc", "ndimc", "vwm", "vwn", "sa", "sb", "pad", "kwi",
-                 "mfma", "grp", "sk", "ns")
+                 "mfma", "grp", "sk", "ns", "ksw")
 
 
 class sgemm_config(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int) for n in CONFIG_FIELDS] + [("reserved", ctypes.c_int * 1)]
+    _fields_ = [(n, ctypes.c_int) for n in CONFIG_FIELDS]
 
     def as_tuple(self):
         return tuple(getattr(self, n) for n in CONFIG_FIELDS)
@@ -36,17 +36,16 @@ class sgemm_config(ctypes.Structure):
 
 
 def make_config(*args, **kw):
-    """sgemm_config from positional values in field order (the last two, sk and ns, may be
-    left out and are then 1 and 2), or from keywords."""
+    """sgemm_config from positional values in field order (the last three, sk, ns and ksw, may
+    be left out from the right and are then 1, 2 and 1), or from keywords."""
     c = sgemm_config()
-    c.sk, c.ns = 1, 2
+    c.sk, c.ns, c.ksw = 1, 2, 1
     if args:
-        if len(args) == len(CONFIG_FIELDS) - 2:
-            args = tuple(args) + (1,)
-        if len(args) == len(CONFIG_FIELDS) - 1:
-            args = tuple(args) + (2,)
-        if len(args) != len(CONFIG_FIELDS):
-            raise ValueError("expected %d values" % len(CONFIG_FIELDS))
+        tail = (1, 2, 1)
+        missing = len(CONFIG_FIELDS) - len(args)
+        if not 0 <= missing <= 3:
+            raise ValueError("expected %d to %d values" % (len(CONFIG_FIELDS) - 3, len(CONFIG_FIELDS)))
+        args = tuple(args) + tail[3 - missing:]
         kw = dict(zip(CONFIG_FIELDS, args))
     for k, v in kw.items():
         if k not in CONFIG_FIELDS:

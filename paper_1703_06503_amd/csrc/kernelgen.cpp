@@ -1,4 +1,5 @@
 #include "kernelgen.h"
+#include "space.h"
 
 #include <dlfcn.h>
 #include <hip/hiprtc.h>
@@ -137,7 +138,10 @@ std::string VariantKey::macros() const {
                   cfg.mwg, cfg.nwg, cfg.kwg, cfg.mdimc, cfg.ndimc, cfg.vwm, cfg.vwn, cfg.sa, cfg.sb,
                   cfg.pad, cfg.kwi, cfg.mfma, cfg.grp, cfg.ns > 0 ? cfg.ns : 2, layout & 1,
                   (layout >> 1) & 1, edge ? 1 : 0, splitk ? 1 : 0);
-    return buf;
+    std::string out = buf;
+    // only where it differs from the source's default: builds without it keep their cache names
+    if (cfg.ksw > 1) out += " -DKSW=" + std::to_string(cfg.ksw);
+    return out;
 }
 
 void set_cache_dir(const std::string &path) {
@@ -312,7 +316,7 @@ LoadedKernel::~LoadedKernel() {
 }
 
 int load_kernel(const VariantKey &key, std::shared_ptr<LoadedKernel> *out, std::string *log) {
-    return load_kernel(gemm_source(), key.macros(), key.cfg.mdimc * key.cfg.ndimc, out, log);
+    return load_kernel(gemm_source(), key.macros(), threads_of(key.cfg), out, log);
 }
 
 int load_kernel(const KernelSource &source, const std::string &macros, int threads,

@@ -102,11 +102,12 @@ int load_cache_file_locked(const char *path) {
         float ms;
         Point p;
         p[13] = 1; // older files have no SK column ...
-        p[14] = 2; // ... and no NS column
-        const int got = std::sscanf(line, "%d %d %d %d %f %d %d %d %d %d %d %d %d %d %d %d %d %d %d %d", &M,
+        p[14] = 2; // ... no NS column ...
+        p[15] = 1; // ... and no KSW column
+        const int got = std::sscanf(line, "%d %d %d %d %f %d %d %d %d %d %d %d %d %d %d %d %d %d %d %d %d", &M,
                                     &N, &K, &layout, &ms, &p[0], &p[1], &p[2], &p[3], &p[4], &p[5],
-                                    &p[6], &p[7], &p[8], &p[9], &p[10], &p[11], &p[12], &p[13], &p[14]);
-        if (got < 18 || got > 20) continue;
+                                    &p[6], &p[7], &p[8], &p[9], &p[10], &p[11], &p[12], &p[13], &p[14], &p[15]);
+        if (got < 18 || got > 21) continue;
         sgemm_config c = from_point(p);
         if (violates_structure(c) || M < 0 || N < 0 || K < 0 || layout < 0 || layout > 3) continue;
         g_tuned[ShapeKey{M, N, K, layout}] = Tuned{c, ms};
@@ -163,6 +164,7 @@ sgemm_config default_config(int M, int N, int K) {
     c.mdimc = c.ndimc = best->dim;
     c.mfma = best->mfma;
     c.kwg = 32; c.vwm = 4; c.vwn = 4; c.sa = 1; c.sb = 1; c.pad = 1; c.kwi = 8; c.grp = 1; c.ns = 2;
+    c.ksw = 1;
     c.sk = best_sk;
     return c;
 }
@@ -1055,7 +1057,7 @@ int sgemm_cache_save(const char *path) {
     autoload_locked();
     FILE *f = std::fopen(path, "w");
     if (!f) return SGEMM_E_IO;
-    std::fprintf(f, "# M N K layout ms MWG NWG KWG MDIMC NDIMC VWM VWN SA SB PAD KWI MFMA GRP SK NS\n");
+    std::fprintf(f, "# M N K layout ms MWG NWG KWG MDIMC NDIMC VWM VWN SA SB PAD KWI MFMA GRP SK NS KSW\n");
     for (auto &kv : g_tuned) {
         const Point p = to_point(kv.second.cfg);
         std::fprintf(f, "%d %d %d %d %.6g", std::get<0>(kv.first), std::get<1>(kv.first),

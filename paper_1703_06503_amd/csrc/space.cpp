@@ -7,22 +7,25 @@
 namespace sgemm {
 
 static const char *kNames[kDims] = {"MWG", "NWG", "KWG", "MDIMC", "NDIMC", "VWM", "VWN",
-                                    "SA",  "SB",  "PAD", "KWI",   "MFMA",  "GRP",   "SK",  "NS"};
+                                    "SA",  "SB",  "PAD", "KWI",   "MFMA",  "GRP",   "SK",  "NS", "KSW"};
 
 const char *dim_name(int d) { return (d >= 0 && d < kDims) ? kNames[d] : "?"; }
 
 Point to_point(const sgemm_config &c) {
     return Point{c.mwg, c.nwg, c.kwg, c.mdimc, c.ndimc, c.vwm, c.vwn,
-                 c.sa,  c.sb,  c.pad, c.kwi,   c.mfma,  c.grp, c.sk > 0 ? c.sk : 1, c.ns > 0 ? c.ns : 2};
+                 c.sa,  c.sb,  c.pad, c.kwi,   c.mfma,  c.grp, c.sk > 0 ? c.sk : 1, c.ns > 0 ? c.ns : 2,
+                 c.ksw > 0 ? c.ksw : 1};
 }
 
 sgemm_config from_point(const Point &p) {
     sgemm_config c{};
     c.mwg = p[0]; c.nwg = p[1]; c.kwg = p[2]; c.mdimc = p[3]; c.ndimc = p[4];
     c.vwm = p[5]; c.vwn = p[6]; c.sa = p[7]; c.sb = p[8]; c.pad = p[9];
-    c.kwi = p[10]; c.mfma = p[11]; c.grp = p[12]; c.sk = p[13]; c.ns = p[14];
+    c.kwi = p[10]; c.mfma = p[11]; c.grp = p[12]; c.sk = p[13]; c.ns = p[14]; c.ksw = p[15];
     return c;
 }
+
+int threads_of(const sgemm_config &c) { return c.mdimc * c.ndimc * (c.ksw > 1 ? c.ksw : 1); }
 
 int lds_bytes(const sgemm_config &c, int layout) {
     // only register-staged tiles can be padded; LDS-direct tiles are dense
@@ -30,7 +33,10 @@ int lds_bytes(const sgemm_config &c, int layout) {
     int words = 0;
     if (c.sa) words += (layout & 1) ? c.kwg * (c.mwg + pad_a) : c.mwg * (c.kwg + pad_a);
     if (c.sb) words += (layout & 2) ? c.nwg * (c.kwg + pad_b) : c.kwg * (c.nwg + pad_b);
-    return (c.ns > 0 ? c.ns : 2) * 4 * words; // ns buffers of floats
+    words *= (c.ns > 0 ? c.ns : 2); // ns buffers
+    // wave groups hand their sums over through the same memory, one tile of C at a time
+    if (c.ksw > 1 && c.mwg * c.nwg > words) words = c.mwg * c.nwg;
+    return 4 * words;
 }
 
 int lds_bytes(const sgemm_config &c) {
@@ -56,7 +62,7 @@ static bool is_tile_edge(int v, int lo, int hi) {
 // being multiplied and the one fetched ahead), the global->LDS staging registers, two address
 // registers per global load instruction of a slab, and 24 for loop state and the epilogue.
 int estimated_registers(const sgemm_config &c) {
-    const int nt = c.mdimc * c.ndimc;
+    const int nt = threads_of(c);
     const int mwi = c.mwg / c.mdimc, nwi = c.nwg / c.ndimc;
     int fragments;
     if (c.mfma) {
@@ -76,7 +82,7 @@ int estimated_registers(const sgemm_config &c) {
 static int register_budget(int nt) { return 512 / ((nt + 255) / 256); }
 
 int direct_loads_per_slab(const sgemm_config &c) {
-    const int nt = c.mdimc * c.ndimc;
+    const int nt = threads_of(c);
     int ops = 0;
     if (c.sa == 2) ops += c.mwg * c.kwg / (nt * c.vwm);
     if (c.sb == 2) ops += c.nwg * c.kwg / (nt * c.vwn);
@@ -85,7 +91,7 @@ int direct_loads_per_slab(const sgemm_config &c) {
 
 const char *violates(const sgemm_config &c) {
     if (const char *why = violates_structure(c)) return why;
-    const int nt = c.mdimc * c.ndimc;
+    const int nt = threads_of(c);
     const int mwi = c.mwg / c.mdimc, nwi = c.nwg / c.ndimc;
     // device limit: the register file (without the matrix cores there are no accumulation
     // registers, so 256 at most)
@@ -108,13 +114,15 @@ const char *violates_structure(const sgemm_config &c) {
     if (c.mfma < 0 || c.mfma > 2) return "MFMA";
     if (!is_pow2_between(c.kwi, 1, 32)) return "KWI";
     if (c.sk < 0 || c.sk > kMaxSplitK) return "SK"; // 0 is read as 1
-    if (c.reserved[0]) return "reserved field set";
-    const int nt = c.mdimc * c.ndimc;
+    if (c.ksw != 0 && c.ksw != 1 && c.ksw != 2 && c.ksw != 4) return "KSW"; // 0 is read as 1
+    if (c.ksw > 1 && !c.mfma) return "KSW > 1 without the matrix-core schedule";
+    const int ksw = c.ksw > 1 ? c.ksw : 1;
+    const int nt = threads_of(c);
     // device limit: whole wavefronts, at most 1024 threads
-    if (nt % 64 != 0 || nt > kMaxThreads) return "threads per workgroup";
+    if ((c.mdimc * c.ndimc) % 64 != 0 || nt > kMaxThreads) return "threads per workgroup";
     if (c.mwg % c.mdimc || c.nwg % c.ndimc) return "tile not divisible by workgroup shape";
     const int mwi = c.mwg / c.mdimc, nwi = c.nwg / c.ndimc;
-    if (c.kwg % c.kwi) return "KWG not divisible by KWI";
+    if (c.kwg % (c.kwi * ksw)) return "KWG not divisible by KWI (times KSW)";
     if (c.sa) {
         if (c.mwg % c.vwm || c.kwg % c.vwm) return "A tile row not divisible by VWM";
         if ((c.mwg * c.kwg) % (nt * c.vwm)) return "A tile not divisible among threads";
@@ -169,27 +177,32 @@ static Space build(int preset) {
     switch (preset) {
     case SGEMM_SPACE_SMALL:
         // MWG, NWG in {32,64}; KWG in {8,16}; staging on/off for both operands together
-        s.values = {{32, 64}, {32, 64}, {8, 16}, {8}, {8}, {1}, {1}, {0, 1}, {0, 1}, {0}, {2}, {0}, {0}, {1}, {2}};
+        s.values = {{32, 64}, {32, 64}, {8, 16}, {8}, {8}, {1}, {1}, {0, 1}, {0, 1}, {0}, {2}, {0}, {0}, {1}, {2}, {1}};
         break;
     case SGEMM_SPACE_FULL:
         s.values = {{32, 64, 128, 256}, {32, 64, 128, 256}, {8, 16, 32}, {8, 16}, {8, 16},
-                    {1, 4}, {1, 4}, {0, 1}, {0, 1}, {0, 1}, {2, 8}, {0, 1}, {0, 1}, {1}, {2}};
+                    {1, 4}, {1, 4}, {0, 1}, {0, 1}, {0, 1}, {2, 8}, {0, 1}, {0, 1}, {1}, {2}, {1}};
         break;
     case SGEMM_SPACE_MFMA:
         s.values = {{64, 128, 256}, {64, 128, 256}, {8, 16, 32}, {8, 16, 32}, {8, 16, 32},
-                    {1, 2, 4}, {1, 2, 4}, {1}, {1}, {0, 1}, {2, 8}, {1, 2}, {0, 1}, {1}, {2}};
+                    {1, 2, 4}, {1, 2, 4}, {1}, {1}, {0, 1}, {2, 8}, {1, 2}, {0, 1}, {1}, {2}, {1}};
         break;
     case SGEMM_SPACE_EXT:
         // matrix-core variants with tile edges 3 * 2^a as well, deeper K slabs, and split K
         s.values = {{32, 64, 96, 128, 192, 256}, {32, 64, 96, 128, 192, 256}, {16, 32, 64},
                     {8, 16, 32}, {8, 16, 32}, {1, 2, 4}, {1, 2, 4}, {1}, {1}, {0, 1}, {2, 8},
-                    {1, 2}, {0, 1}, {1, 2, 3, 4, 6, 8, 12, 16}, {2}};
+                    {1, 2}, {0, 1}, {1, 2, 3, 4, 6, 8, 12, 16}, {2}, {1}};
         break;
     case SGEMM_SPACE_DIRECT:
         // matrix-core variants fed by LDS-direct loads, 2 to 4 LDS buffers per tile
         s.values = {{32, 64, 96, 128, 192, 256}, {32, 64, 96, 128, 192, 256}, {16, 32, 64},
                     {8, 16, 32}, {8, 16, 32}, {1, 4}, {1, 4}, {2}, {2}, {0}, {2, 8},
-                    {1, 2}, {0, 1}, {1, 2, 3, 4, 6, 8, 12, 16}, {2, 3, 4}};
+                    {1, 2}, {0, 1}, {1, 2, 3, 4, 6, 8, 12, 16}, {2, 3, 4}, {1}};
+        break;
+    case SGEMM_SPACE_KSPLIT:
+        // matrix-core variants whose waves share out the K slab: small tiles, 2 or 4 wave groups
+        s.values = {{32, 64, 96, 128}, {32, 64, 96, 128}, {32, 64}, {8, 16}, {8, 16}, {4}, {4}, {1}, {1},
+                    {0, 1}, {2, 8}, {1, 2}, {0, 1}, {1, 2, 4}, {2}, {2, 4}};
         break;
     default:
         s.preset = -1;
@@ -219,7 +232,7 @@ static Space build(int preset) {
 // ---- the caller-defined space ---------------------------------------------------------------
 // "NAME=v,v,... NAME=v ..." (names as in dim_name(), separated by blanks or ';'); a parameter
 // that is not named keeps the single value given as its default here.
-static const int kCustomDefaults[kDims] = {128, 128, 32, 16, 16, 4, 4, 1, 1, 1, 8, 1, 0, 1, 2};
+static const int kCustomDefaults[kDims] = {128, 128, 32, 16, 16, 4, 4, 1, 1, 1, 8, 1, 0, 1, 2, 1};
 
 static bool parse_custom(const std::string &spec, std::vector<std::vector<int>> *values) {
     values->assign(kDims, {});

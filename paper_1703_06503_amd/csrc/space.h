@@ -13,7 +13,7 @@
 
 namespace sgemm {
 
-constexpr int kDims = 15;              // tuned fields of sgemm_config, in field order
+constexpr int kDims = 16;              // tuned fields of sgemm_config, in field order
 constexpr int kLdsLimitBytes = 163840; // LDS per workgroup on gfx950
 constexpr int kMaxThreads = 1024;
 constexpr int kMaxSplitK = 64;         // upper bound of the SK parameter
@@ -30,6 +30,7 @@ int lds_bytes(const sgemm_config &c);       // worst case over the four storage 
 int lds_bytes(const sgemm_config &c, int layout);
 int estimated_registers(const sgemm_config &c); // beside the accumulators
 int direct_loads_per_slab(const sgemm_config &c); // LDS-direct load instructions per thread
+int threads_of(const sgemm_config &c);            // mdimc * ndimc * ksw
 
 // nullptr if c satisfies every constraint, else a short reason.
 const char *violates(const sgemm_config &c);

@@ -10,7 +10,7 @@ import os
 import sys
 
 FIELDS = ("MWG", "NWG", "KWG", "MDIMC", "NDIMC", "VWM", "VWN", "SA", "SB", "PAD", "KWI", "MFMA",
-          "GRP", "SK", "NS")
+          "GRP", "SK", "NS", "KSW")
 LAYOUTS = {0: "A M×K, B K×N", 1: "A K×M, B K×N", 2: "A M×K, B N×K", 3: "A K×M, B N×K"}
 
 
@@ -26,7 +26,7 @@ def read_table(path):
             M, N, K, layout = (int(x) for x in p[:4])
             ms = float(p[4])
             cfg = [int(x) for x in p[5:]]
-            cfg += [1, 2][len(cfg) - 13:]          # SK and NS columns of older tables
+            cfg += [1, 2, 1][len(cfg) - 13:]       # SK, NS and KSW columns of older tables
             rows.append((M, N, K, layout, ms, cfg))
     return rows
 

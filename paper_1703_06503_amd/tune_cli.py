@@ -12,7 +12,7 @@ import sys
 import time
 
 STRATEGIES = {"full": 0, "random": 1, "annealing": 2, "pso": 3}
-SPACES = {"full": 0, "small": 1, "mfma": 2, "ext": 3, "direct": 4, "custom": 5}
+SPACES = {"full": 0, "small": 1, "mfma": 2, "ext": 3, "direct": 4, "custom": 5, "ksplit": 6}
 
 
 def main(argv=None):

@@ -175,13 +175,19 @@ def test_per_shape_cache_roundtrip(tmp_path):
     b.sgemm_cache_load(path)
     assert b.sgemm_cache_count() == 2
     assert b.sgemm_config_get(4096, 4096, 4096, 0).as_tuple() == c2.as_tuple()
-    # a table written before the SK and NS columns existed still loads (SK = 1, NS = 2)
+    # a table written before the SK, NS and KSW columns existed still loads (SK = 1, NS = 2, KSW = 1)
     old = tmp_path / "old.txt"
     old.write_text("# M N K layout ms MWG NWG KWG MDIMC NDIMC VWM VWN SA SB PAD KWI MFMA GRP\n"
                    "1024 1024 1024 0 0.05 128 128 16 16 16 4 4 1 1 1 8 1 1\n")
     b.sgemm_cache_load(str(old))
     got = b.sgemm_config_get(1024, 1024, 1024, 0)
-    assert got.as_tuple() == (128, 128, 16, 16, 16, 4, 4, 1, 1, 1, 8, 1, 1, 1, 2)
+    assert got.as_tuple() == (128, 128, 16, 16, 16, 4, 4, 1, 1, 1, 8, 1, 1, 1, 2, 1)
+    c3 = b.make_config(64, 64, 64, 16, 16, 4, 4, 1, 1, 1, 8, 1, 1, 2, 2, 4)      # wave groups share K
+    b.sgemm_config_set(800, 800, 800, 0, c3, 0.02)
+    b.sgemm_cache_save(path)
+    b.sgemm_cache_clear()
+    b.sgemm_cache_load(path)
+    assert b.sgemm_config_get(800, 800, 800, 0).as_tuple() == c3.as_tuple()
     with pytest.raises(b.SgemmError) as e:
         b.sgemm_cache_load(str(tmp_path / "missing.txt"))
     assert e.value.status == b.E_IO

@@ -12,7 +12,7 @@ pytestmark = pytest.mark.gpu
 
 # The fixed samples of the spaces, the shapes and the hand-picked configurations live in
 # tests/variants.py (also read by tests/precompile_test_variants.py).
-from tests.variants import (FULL_SAMPLE, MFMA_SAMPLE, EXT_SAMPLE, DIRECT_SAMPLE, EXACT_EXT, RAGGED_EXT,  # noqa: E402
+from tests.variants import (FULL_SAMPLE, MFMA_SAMPLE, EXT_SAMPLE, DIRECT_SAMPLE, KSPLIT_SAMPLE, EXACT_EXT, RAGGED_EXT,  # noqa: E402
                             EXACT_SHAPE, RAGGED_SHAPE, NARROW_SHAPE, RAGGED_BIG, ODD_SHAPE, BENCH_CONFIGS,
                             SKINNY_CONFIGS, sample_configs)
 from tests.variants import some_configs as _some_configs  # noqa: E402
@@ -78,6 +78,22 @@ def test_direct_space_sample_ragged():
     _sweep(b.SPACE_DIRECT, idx[::4], ODD_SHAPE, 1.0, 1.0, 0, seed=29)
 
 
+def test_ksplit_space_sample():
+    """Variants whose waves share out the K slab (KSW 2 and 4): exact tiles, ragged sizes, and
+    odd sizes whose stored rows end inside a load vector."""
+    idx = sample_configs(**KSPLIT_SAMPLE)
+    _sweep(b.SPACE_KSPLIT, idx, EXACT_EXT, 1.0, 0.0, 0, seed=31, dist="normal")
+    _sweep(b.SPACE_KSPLIT, idx, RAGGED_EXT, -0.5, 2.0, 0, seed=32)
+    _sweep(b.SPACE_KSPLIT, idx[::4], ODD_SHAPE, 1.0, 1.0, 0, seed=33)
+
+
+@pytest.mark.parametrize("layout", [1, 2, 3])
+def test_ksplit_space_transposed_storage(layout):
+    idx = sample_configs(b.SPACE_KSPLIT, 16, seed=400 + layout)
+    _sweep(b.SPACE_KSPLIT, idx, EXACT_EXT, 1.0, 0.0, layout, seed=34 + layout)
+    _sweep(b.SPACE_KSPLIT, idx, RAGGED_EXT, 1.5, -0.5, layout, seed=37 + layout)
+
+
 @pytest.mark.parametrize("layout", [1, 2, 3])
 def test_direct_space_transposed_storage(layout):
     idx = sample_configs(b.SPACE_DIRECT, 24, seed=300 + layout)
@@ -98,7 +114,7 @@ def test_transposed_storage(layout):
     _sweep(b.SPACE_FULL, idx, RAGGED_SHAPE, 0.5, 2.0, layout, seed=40 + layout)
 
 
-WHICH = list(range(9))
+WHICH = list(range(12))
 
 
 @pytest.mark.parametrize("which", WHICH)
@@ -184,7 +200,7 @@ def _check_leading_dimensions(cfg, M, N, K, lda, ldb, ldc):
 
 
 @pytest.mark.parametrize("layout", [0, 1, 2, 3])
-@pytest.mark.parametrize("which", [0, 1, 4, 6])
+@pytest.mark.parametrize("which", [0, 1, 4, 6, 10])
 def test_padded_path_matches_the_oracle_and_leaves_padding_untouched(which, layout):
     """Pre-processing instead of guards: zero-padded copies, the unguarded build, copy back."""
     import torch
@@ -277,7 +293,7 @@ def test_reference_kernel_against_oracle():
         assert np.max(np.abs(got - ref)) <= 2.0 ** -23 * np.max(np.abs(ref))
 
 
-@pytest.mark.parametrize("which", [1, 4, 5, 7])
+@pytest.mark.parametrize("which", [1, 4, 5, 7, 9, 10])
 def test_run_to_run_determinism(which):
     """No atomics anywhere: split-K planes are added in index order by the reduction kernel."""
     cfg = _some_configs()[which]

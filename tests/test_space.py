@@ -10,14 +10,14 @@ from paper_1703_06503_amd import binding as b
 
 
 @pytest.mark.parametrize("preset", [b.SPACE_FULL, b.SPACE_SMALL, b.SPACE_MFMA, b.SPACE_EXT,
-                                    b.SPACE_DIRECT])
+                                    b.SPACE_DIRECT, b.SPACE_KSPLIT])
 def test_space_equals_oracle_enumeration(preset):
     want = so.enumerate_space(preset)
     n = b.sgemm_space_size(preset)
     assert n == len(want)
     assert b.sgemm_space_raw_size(preset) == so.raw_size(preset)
-    assert b.sgemm_space_dims(preset) == len(so.NAMES) == 15
-    for d in range(15):
+    assert b.sgemm_space_dims(preset) == len(so.NAMES) == 16
+    for d in range(16):
         assert b.sgemm_space_values(preset, d) == list(so.VALUES[preset][d])
     step = 1 if n < 2000 else (7 if n < 50000 else 101)
     for i in list(range(0, n, step)) + [n - 1]:
@@ -36,7 +36,7 @@ def test_sizes():
 def test_config_check_agrees_with_oracle_on_the_raw_product():
     """Every point of the raw cartesian product of a preset, valid or not."""
     import itertools
-    for preset in (b.SPACE_SMALL, b.SPACE_MFMA, b.SPACE_EXT, b.SPACE_DIRECT):
+    for preset in (b.SPACE_SMALL, b.SPACE_MFMA, b.SPACE_EXT, b.SPACE_DIRECT, b.SPACE_KSPLIT):
         lists = so.VALUES[preset]
         rng = np.random.default_rng(preset)
         for _ in range(1500):
@@ -45,14 +45,15 @@ def test_config_check_agrees_with_oracle_on_the_raw_product():
 
 
 def test_every_emitted_config_meets_the_device_limits():
-    for preset in (b.SPACE_FULL, b.SPACE_MFMA, b.SPACE_EXT, b.SPACE_DIRECT):
+    for preset in (b.SPACE_FULL, b.SPACE_MFMA, b.SPACE_EXT, b.SPACE_DIRECT, b.SPACE_KSPLIT):
         n = b.sgemm_space_size(preset)
         for i in range(0, n, 11 if n < 50000 else 173):
             c = b.sgemm_space_get(preset, i)
             t = c.as_tuple()
-            threads = c.mdimc * c.ndimc
+            threads = c.mdimc * c.ndimc * c.ksw
             assert threads % 64 == 0 and threads <= 1024
-            assert c.mwg % c.mdimc == 0 and c.nwg % c.ndimc == 0 and c.kwg % c.kwi == 0
+            assert c.mwg % c.mdimc == 0 and c.nwg % c.ndimc == 0 and c.kwg % (c.kwi * c.ksw) == 0
+            assert c.ksw == 1 or c.mfma
             lds = b.sgemm_config_lds_bytes(c)
             assert lds == so.worst_lds_bytes(t) <= 160 * 1024
             if c.sa:
@@ -85,7 +86,8 @@ def test_invalid_examples():
     assert b.sgemm_config_check(b.make_config(*ok)) == 0
     for field, value in [("mwg", 80), ("mwg", 48), ("kwg", 12), ("mdimc", 4), ("vwm", 3), ("kwi", 32),
                          ("mfma", 3), ("sa", 3), ("mwg", 1024), ("sk", -1), ("sk", 65), ("ns", 1), ("ns", 5),
-                         ("ns", 3)]:      # three buffers need LDS-direct staging
+                         ("ns", 3),       # three buffers need LDS-direct staging
+                         ("ksw", 3), ("ksw", 8), ("ksw", 4)]:      # 16 is not divisible by 8 * 4
         c = b.make_config(*ok)
         setattr(c, field, value)
         assert b.sgemm_config_check(c) == b.E_INVALID, (field, value)
@@ -101,13 +103,13 @@ def test_predicted_lds_size_matches_the_compiled_variants(tmp_path):
     import os
     b.sgemm_kernel_cache_dir(str(tmp_path))
     try:
-        for preset in (b.SPACE_FULL, b.SPACE_MFMA, b.SPACE_EXT, b.SPACE_DIRECT):
+        for preset in (b.SPACE_FULL, b.SPACE_MFMA, b.SPACE_EXT, b.SPACE_DIRECT, b.SPACE_KSPLIT):
             n = b.sgemm_space_size(preset)
             rng = np.random.default_rng(100 + preset)
             checked = 0
             for i in rng.choice(n, size=40, replace=False):
                 c = b.sgemm_space_get(preset, int(i))
-                if c.mdimc * c.ndimc > 256 or c.mwg * c.nwg > 128 * 128:
+                if c.mdimc * c.ndimc * c.ksw > 256 or c.mwg * c.nwg > 128 * 128:
                     continue            # keep to variants that compile in about a second
                 t = c.as_tuple()
                 layout = max(range(4), key=lambda l: so.lds_bytes(t, l))
@@ -135,8 +137,9 @@ def compile_raw(cfg, layout=0, edge=0):
     """Compile the kernel family's source for ANY parameter values, valid or not, through the
     generic tuner (which knows nothing of the GEMM constraints); returns the compiler's report
     or raises SgemmError with the compiler's message."""
+    ksw = cfg[15] if len(cfg) > 15 else 1
     text = (f"#define TRA {layout & 1}\n#define TRB {layout >> 1}\n#define EDGE {edge}\n#define NS {cfg[14]}\n"
-            + open(KERNEL_SOURCE).read())
+            f"#define KSW {ksw}\n" + open(KERNEL_SOURCE).read())
     t = b.ktuner_create(text, "sgemm_variant", (64, 1, 1), (64, 1, 1))
     try:
         for name, value in zip(MACRO_NAMES, cfg):
@@ -154,8 +157,8 @@ def test_register_model_against_the_compiler():
     also in the riskiest corner, where the accumulators take half of the budget."""
     rng = np.random.default_rng(77)
     sample = []
-    for preset in (so.SPACE_FULL, so.SPACE_MFMA, so.SPACE_EXT, so.SPACE_DIRECT):
-        space = so.enumerate_space(preset) if preset in (so.SPACE_FULL, so.SPACE_MFMA) else None
+    for preset in (so.SPACE_FULL, so.SPACE_MFMA, so.SPACE_EXT, so.SPACE_DIRECT, so.SPACE_KSPLIT):
+        space = so.enumerate_space(preset) if preset in (so.SPACE_FULL, so.SPACE_MFMA, so.SPACE_KSPLIT) else None
         if space is None:      # the two large presets: draw from the raw product, keep the valid
             lists = so.VALUES[preset]
             space = []
@@ -164,12 +167,12 @@ def test_register_model_against_the_compiler():
                 if so.valid(cfg):
                     space.append(cfg)
         picks = [space[int(i)] for i in rng.choice(len(space), size=10, replace=False)]
-        corner = [c for c in space if c[11] and 2 * so.register_estimate(c)[0] == so.register_budget(c[3] * c[4])]
+        corner = [c for c in space if c[11] and 2 * so.register_estimate(c)[0] == so.register_budget(c[3] * c[4] * c[15])]
         picks += [corner[int(i)] for i in rng.choice(len(corner), size=min(4, len(corner)), replace=False)]
         sample += picks
     spilled = []
     for cfg in sample:
-        threads = cfg[3] * cfg[4]
+        threads = cfg[3] * cfg[4] * cfg[15]
         acc, other = so.register_estimate(cfg)
         info = b.sgemm_kernel_compile(b.make_config(*cfg), 0, 0)
         # registers reported: architected + accumulation together (unified file)
@@ -177,7 +180,7 @@ def test_register_model_against_the_compiler():
         assert info.vgprs >= acc, (cfg, info.vgprs, acc)
         if info.scratch_bytes > 0:
             spilled.append(cfg)
-    assert len(sample) >= 50
+    assert len(sample) >= 60
     assert len(spilled) <= 2, spilled           # under 4 % of the sample, corner cases included
 
 
@@ -186,11 +189,11 @@ def test_what_the_register_model_rejects_does_spill():
     rule holds), one per rule: they compile, and the compiler reports spills."""
     cases = [
         # 16x16x4 tiles with all 256 accumulation registers taken by accumulators
-        (256, 256, 16, 16, 16, 4, 4, 1, 1, 1, 8, 2, 0, 1, 2),
+        (256, 256, 16, 16, 16, 4, 4, 1, 1, 1, 8, 2, 0, 1, 2, 1),
         # 1024 threads leave 128 registers per lane: 64 accumulators and the rest do not fit
-        (256, 256, 16, 32, 32, 4, 4, 1, 1, 1, 8, 1, 0, 1, 2),
+        (256, 256, 16, 32, 32, 4, 4, 1, 1, 1, 8, 1, 0, 1, 2, 1),
         # one wave, 256 accumulators, and 160 staging registers on top
-        (64, 256, 32, 8, 8, 4, 4, 1, 1, 1, 8, 1, 0, 1, 2),
+        (64, 256, 32, 8, 8, 4, 4, 1, 1, 1, 8, 1, 0, 1, 2, 1),
     ]
     for cfg in cases:
         assert not so.registers_fit(cfg) and not so.valid(cfg), cfg
@@ -209,8 +212,8 @@ def test_loads_in_flight_rule_is_what_the_kernel_itself_asserts():
     """More than two LDS buffers keep the loads of NS - 2 slabs in flight behind the slab that
     is waited for, and the wait is a 6-bit count: the kernel source refuses to compile beyond
     63.  The oracle's rule draws the same line: 2 x 32 loads is rejected, 1 x 32 is admitted."""
-    four = (64, 64, 64, 16, 16, 1, 1, 2, 2, 0, 8, 1, 0, 1, 4)      # 32 loads per slab and thread
-    three = four[:14] + (3,)
+    four = (64, 64, 64, 16, 16, 1, 1, 2, 2, 0, 8, 1, 0, 1, 4, 1)      # 32 loads per slab and thread
+    three = four[:14] + (3, 1)
     assert so.valid(three) and not so.valid(four)
     assert b.sgemm_config_check(b.make_config(*three)) == 0
     assert b.sgemm_config_check(b.make_config(*four)) == b.E_INVALID

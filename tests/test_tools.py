@@ -14,7 +14,7 @@ def test_report_reads_old_and_new_tables(tmp_path):
                  "garbage line\n")
     rows = report.read_table(str(t))
     assert len(rows) == 3
-    assert rows[1][5] == [128, 128, 16, 16, 16, 4, 4, 1, 1, 1, 8, 1, 1, 1, 2]
+    assert rows[1][5] == [128, 128, 16, 16, 16, 4, 4, 1, 1, 1, 8, 1, 1, 1, 2, 1]
     out = io.StringIO()
     with contextlib.redirect_stdout(out):
         assert report.main([str(t), "--peak-tflops", "157.3"]) == 0

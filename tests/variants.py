@@ -18,6 +18,7 @@ FULL_SAMPLE = dict(space=b.SPACE_FULL, count=160, seed=1234)
 MFMA_SAMPLE = dict(space=b.SPACE_MFMA, count=80, seed=4321)
 EXT_SAMPLE = dict(space=b.SPACE_EXT, count=80, seed=777)   # tile edges 96/192, split K
 DIRECT_SAMPLE = dict(space=b.SPACE_DIRECT, count=80, seed=555)   # LDS-direct staging, 2-4 buffers
+KSPLIT_SAMPLE = dict(space=b.SPACE_KSPLIT, count=64, seed=999)   # wave groups share out the K slab
 EXACT_EXT = (768, 768, 1024)      # multiples of 96, 192 and 256; 16..64 slabs to split
 RAGGED_EXT = (300, 520, 1000)
 EXACT_SHAPE = (256, 512, 96)      # multiples of every tile size: unguarded variants
@@ -37,7 +38,12 @@ def all_sweeps():
            (b.SPACE_EXT, ext, EXACT_EXT, 0), (b.SPACE_EXT, ext, RAGGED_EXT, 0),
            (b.SPACE_DIRECT, direct, EXACT_EXT, 0), (b.SPACE_DIRECT, direct, RAGGED_EXT, 0),
            (b.SPACE_DIRECT, direct[::4], ODD_SHAPE, 0)]
+    ksplit = sample_configs(**KSPLIT_SAMPLE)
+    out += [(b.SPACE_KSPLIT, ksplit, EXACT_EXT, 0), (b.SPACE_KSPLIT, ksplit, RAGGED_EXT, 0),
+            (b.SPACE_KSPLIT, ksplit[::4], ODD_SHAPE, 0)]
     for layout in (1, 2, 3):
+        k = sample_configs(b.SPACE_KSPLIT, 16, seed=400 + layout)
+        out += [(b.SPACE_KSPLIT, k, EXACT_EXT, layout), (b.SPACE_KSPLIT, k, RAGGED_EXT, layout)]
         d = sample_configs(b.SPACE_DIRECT, 24, seed=300 + layout)
         out += [(b.SPACE_DIRECT, d, EXACT_EXT, layout), (b.SPACE_DIRECT, d, RAGGED_EXT, layout),
                 (b.SPACE_EXT, sample_configs(b.SPACE_EXT, 24, seed=200 + layout), RAGGED_EXT, layout)]
@@ -50,7 +56,9 @@ def some_configs():
     """A vector-ALU variant, a 32x32x2 MFMA variant, a 16x16x4 MFMA variant, and three
     split-K variants (vector ALU, MFMA with a 96-wide tile, MFMA split 16 ways), and three
     variants fed by LDS-direct loads (three LDS buffers; four buffers with split K; vector ALU
-    with A direct and B through registers)."""
+    with A direct and B through registers), and three whose waves share out the K slab (four
+    groups of 32x32 wave tiles; two groups of 16x16x4 tiles with split K on top; four groups fed
+    by LDS-direct loads)."""
     return [
         b.make_config(64, 64, 16, 8, 8, 4, 4, 1, 1, 1, 8, 0, 0),
         b.make_config(128, 128, 16, 16, 16, 4, 4, 1, 1, 1, 8, 1, 1),
@@ -61,6 +69,9 @@ def some_configs():
         b.make_config(128, 128, 16, 16, 16, 4, 4, 2, 2, 0, 8, 1, 1, 1, 3),
         b.make_config(64, 64, 32, 8, 8, 4, 4, 2, 2, 0, 8, 2, 0, 2, 4),
         b.make_config(64, 64, 16, 8, 8, 4, 4, 2, 1, 1, 8, 0, 0, 1, 2),
+        b.make_config(64, 64, 64, 16, 16, 4, 4, 1, 1, 1, 8, 1, 1, 1, 2, 4),
+        b.make_config(32, 64, 64, 8, 16, 4, 4, 1, 1, 0, 8, 2, 0, 2, 2, 2),
+        b.make_config(64, 32, 32, 8, 8, 4, 4, 2, 2, 0, 2, 1, 1, 1, 2, 4),
     ]
 
 
