@@ -40,9 +40,9 @@ MEASURED_TRAFFIC_BYTES = {
     # XCD-aware order, each XCD a 4 x 8 block of tiles: 384 MiB fetched + 64 MiB written
     ("cfg4_4096", (256, 256, 1, 1)): (196657 * 1.9989 + 65536) * 1024,
     # profiles/sgemm_tuned_cfg1_256.txt, sgemm_tuned_cfg5_*.txt (GEMM launch + plane reduction)
-    ("cfg1_256", (64, 32, 1, 1)): (2.30 + 0.25) * 2 ** 20,
+    ("cfg1_256", (32, 32, 0, 1)): (2.28 + 0.25) * 2 ** 20,
     ("cfg5_128x4096x4096", (64, 64, 1, 4)): (80.02 + 8.00 + 8.03 + 2.00) * 2 ** 20,
-    ("cfg5_4096x64x9216", (64, 64, 0, 8)): (161.97 + 8.00 + 8.03 + 1.00) * 2 ** 20,
+    ("cfg5_4096x64x9216", (64, 64, 0, 8)): (161.99 + 8.00 + 8.03 + 1.00) * 2 ** 20,
     # profiles/sgemm_tuned_cfg3_*.txt, cfg2_2048, cfg4_8192
     ("cfg3_1000", (64, 64, 1, 1)): (27.84 + 3.81) * 2 ** 20,
     ("cfg3_1536", (96, 96, 1, 1)): (63.10 + 9.00) * 2 ** 20,
