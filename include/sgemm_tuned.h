@@ -28,8 +28,9 @@ extern "C" {
 
 /* ---- status codes ---------------------------------------------------------------- */
 #define SGEMM_OK 0
-#define SGEMM_E_BADARG (-1)   /* negative size, leading dimension too small, null pointer
-                                 for a non-empty operand, unknown layout/strategy/preset */
+#define SGEMM_E_BADARG (-1)   /* negative size, leading dimension too small (or lda / ldb
+                                 above SGEMM_MAX_LEADING_DIM), null pointer for a non-empty
+                                 operand, unknown layout/strategy/preset */
 #define SGEMM_E_NOCONFIG (-2) /* the search space holds no valid configuration */
 #define SGEMM_E_COMPILE (-3)  /* the kernel generator failed to compile a variant */
 #define SGEMM_E_LAUNCH (-4)   /* HIP refused a module load, launch, allocation or copy */
@@ -45,7 +46,10 @@ extern "C" {
  * The paper's kernel multiplies A^T by B, i.e. it expects A stored K x M.  Here that
  * storage is selected per call: bit 0 set = A stored K x M (row-major, lda >= M), clear =
  * A stored M x K (lda >= K); bit 1 set = B stored N x K (ldb >= K), clear = B stored K x N
- * (ldb >= N).  C is always M x N row-major (ldc >= N).  Leading dimensions in elements. */
+ * (ldb >= N).  C is always M x N row-major (ldc >= N).  Leading dimensions in elements;
+ * lda and ldb at most SGEMM_MAX_LEADING_DIM (a tile of A or B must lie within the 2 GiB that
+ * the kernels address with 32-bit offsets from the tile's origin). */
+#define SGEMM_MAX_LEADING_DIM (1 << 20)
 #define SGEMM_LAYOUT_A_TRANSPOSED 1
 #define SGEMM_LAYOUT_B_TRANSPOSED 2
 
@@ -315,25 +319,31 @@ long long sgemm_config_workspace_bytes(const sgemm_config *cfg, int M, int N, in
 /* [host] Directory of the on-disk code-object cache (default: "kcache" beside the library,
  * or $SGEMM_TUNED_CACHE_DIR). */
 int sgemm_kernel_cache_dir(const char *path);
-/* [host] Compile (or fetch from the cache) the variant for cfg/layout; edge = 1 builds the
- * bounds-guarded form.  cfg must satisfy every constraint but the register estimate (the build
+/* Builds of one configuration (the `build` argument below is a sum of these flags):
+ * guarded against sizes that are not multiples of the tile, and - for calls with beta != 0 on
+ * the matrix-core schedule, where a lane has the registers for it - requesting the old values
+ * of C before the main loop instead of in the epilogue. */
+#define SGEMM_BUILD_GUARDED 1
+#define SGEMM_BUILD_READS_C_AHEAD 2
+/* [host] Compile (or fetch from the cache) the variant for cfg/layout in the given build
+ * (0 = plain, 1 = SGEMM_BUILD_GUARDED as before).  cfg must satisfy every constraint but the register estimate (the build
  * that sgemm_kernel_resolve() names may have narrower load vectors than the configuration it
  * came from and then exceeds the estimate; it still has to be built).  cfg->sk > 1 selects the build that split-K launches use (one build
  * for every sk > 1: the split itself is a launch parameter).  Needs no GPU.  info may be null. */
-int sgemm_kernel_compile(const sgemm_config *cfg, int layout, int edge, sgemm_kernel_info *info);
-/* [host] Which build a call with cfg launches for these sizes and leading dimensions when the
- * operands' pointers are 16-byte aligned: *variant receives the configuration as it is built
- * (vector widths narrowed where a stored row is not a multiple of them, fewer LDS buffers or
- * register staging where narrowed LDS-direct loads no longer fit, sk = 1 when K is not split)
- * and *edge whether it is the guarded build, so that sgemm_kernel_compile(variant, layout,
- * *edge) prepares exactly what the call will load. */
+int sgemm_kernel_compile(const sgemm_config *cfg, int layout, int build, sgemm_kernel_info *info);
+/* [host] Which build a call with cfg launches for these sizes, leading dimensions and beta
+ * (only beta == 0 or not matters) when the operands' pointers are 16-byte aligned: *variant
+ * receives the configuration as it is built (vector widths narrowed where a stored row is not
+ * a multiple of them, fewer LDS buffers or register staging where narrowed LDS-direct loads no
+ * longer fit, sk = 1 when K is not split) and *build the SGEMM_BUILD_* flags, so that
+ * sgemm_kernel_compile(variant, layout, *build) prepares exactly what the call will load. */
 int sgemm_kernel_resolve(const sgemm_config *cfg, int M, int N, int K, int lda, int ldb, int ldc,
-                         int layout, sgemm_config *variant, int *edge);
+                         int layout, float beta, sgemm_config *variant, int *build);
 /* [host] Path of the variant's code object in the cache directory (whether or not it exists
  * yet), NUL-terminated into buf: lets a deployment ship exactly the variants it uses. */
-int sgemm_kernel_cache_path(const sgemm_config *cfg, int layout, int edge, char *buf, int cap);
+int sgemm_kernel_cache_path(const sgemm_config *cfg, int layout, int build, char *buf, int cap);
 /* [host] The -D macro string the variant is compiled with, NUL-terminated into buf. */
-int sgemm_kernel_macros(const sgemm_config *cfg, int layout, int edge, char *buf, int cap);
+int sgemm_kernel_macros(const sgemm_config *cfg, int layout, int build, char *buf, int cap);
 
 /* ---- per-shape best-configuration cache --------------------------------------------- */
 int sgemm_config_get(int M, int N, int K, int layout, sgemm_config *out); /* exact shape only;

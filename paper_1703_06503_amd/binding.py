@@ -16,6 +16,7 @@ E_INVALID, E_IO, E_NODEVICE, E_RESOURCE, E_NOTREADY = -6, -7, -8, -9, -10
 LAYOUT_A_TRANSPOSED, LAYOUT_B_TRANSPOSED = 1, 2
 STRATEGY_FULL, STRATEGY_RANDOM, STRATEGY_ANNEALING, STRATEGY_PSO = 0, 1, 2, 3
 SPACE_FULL, SPACE_SMALL, SPACE_MFMA, SPACE_EXT, SPACE_DIRECT, SPACE_CUSTOM, SPACE_KSPLIT = 0, 1, 2, 3, 4, 5, 6
+BUILD_GUARDED, BUILD_READS_C_AHEAD = 1, 2          # flags of sgemm_kernel_compile / _resolve
 NOALLOC_SCRATCH_BYTES = 32 << 20
 
 CONFIG_FIELDS = ("mwg", "nwg", "kwg", "mdimc", "ndimc", "vwm", "vwn", "sa", "sb", "pad", "kwi",
@@ -205,7 +206,7 @@ def lib():
         L.sgemm_kernel_cache_dir.argtypes = [ctypes.c_char_p]
         L.sgemm_kernel_compile.argtypes = [cfgp, i, i, ctypes.POINTER(sgemm_kernel_info)]
         L.sgemm_kernel_macros.argtypes = [cfgp, i, i, ctypes.c_char_p, i]
-        L.sgemm_kernel_resolve.argtypes = [cfgp, i, i, i, i, i, i, i, cfgp, ctypes.POINTER(i)]
+        L.sgemm_kernel_resolve.argtypes = [cfgp, i, i, i, i, i, i, i, ctypes.c_float, cfgp, ctypes.POINTER(i)]
         L.sgemm_config_get.argtypes = [i, i, i, i, cfgp]
         L.sgemm_config_set.argtypes = [i, i, i, i, cfgp, f]
         L.sgemm_config_select.argtypes = [i, i, i, i, cfgp]
@@ -464,12 +465,12 @@ def sgemm_kernel_cache_path(cfg, layout=0, edge=0):
     return os.fsdecode(buf.value)
 
 
-def sgemm_kernel_resolve(cfg, M, N, K, lda, ldb, ldc, layout=0):
-    """Returns (configuration as built, edge)."""
-    out, edge = sgemm_config(), ctypes.c_int(0)
-    _check(lib().sgemm_kernel_resolve(ctypes.byref(cfg), M, N, K, lda, ldb, ldc, layout,
-                                      ctypes.byref(out), ctypes.byref(edge)), "sgemm_kernel_resolve")
-    return out, edge.value
+def sgemm_kernel_resolve(cfg, M, N, K, lda, ldb, ldc, layout=0, beta=0.0):
+    """Returns (configuration as built, build flags)."""
+    out, build = sgemm_config(), ctypes.c_int(0)
+    _check(lib().sgemm_kernel_resolve(ctypes.byref(cfg), M, N, K, lda, ldb, ldc, layout, float(beta),
+                                      ctypes.byref(out), ctypes.byref(build)), "sgemm_kernel_resolve")
+    return out, build.value
 
 
 def sgemm_kernel_macros(cfg, layout=0, edge=0):

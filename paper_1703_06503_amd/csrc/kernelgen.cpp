@@ -141,6 +141,7 @@ std::string VariantKey::macros() const {
     std::string out = buf;
     // only where it differs from the source's default: builds without it keep their cache names
     if (cfg.ksw > 1) out += " -DKSW=" + std::to_string(cfg.ksw);
+    if (cpf) out += " -DCPF=1";
     return out;
 }
 

@@ -20,6 +20,7 @@ struct VariantKey {
     int layout;
     int edge;
     int splitk = 0; // 1 = the build that split-K launches use (cfg.sk itself is not compiled in)
+    int cpf = 0;    // 1 = the build for beta != 0 that requests the old C before the first slab
     std::string macros() const; // "-DMWG=.. -DNWG=.. ..." in a fixed order
 };
 

@@ -202,6 +202,9 @@ int check_gemm_args(int M, int N, int K, const float *A, int lda, const float *B
         if (!A || !B) return SGEMM_E_BADARG;
         if (lda < ((layout & 1) ? M : K)) return SGEMM_E_BADARG;
         if (ldb < ((layout & 2) ? K : N)) return SGEMM_E_BADARG;
+        // a tile of up to 512 stored rows must lie within the 2 GiB that the kernels' 32-bit
+        // byte offsets (and the buffer windows they read through) can span
+        if (lda > kMaxLeadingDim || ldb > kMaxLeadingDim) return SGEMM_E_BADARG;
     }
     return SGEMM_OK;
 }
@@ -216,10 +219,13 @@ bool aligned_for(const void *p, int ld, int vw) {
 
 // The variant that will really be launched for this call.
 VariantKey resolve_variant(const sgemm_config &cfg, int M, int N, int K, const float *A, int lda,
-                           const float *B, int ldb, const float *C, int ldc, int layout) {
+                           const float *B, int ldb, const float *C, int ldc, int layout, float beta) {
     VariantKey key{cfg, layout, 0};
     key.edge = (M % cfg.mwg || N % cfg.nwg || K % cfg.kwg) ? 1 : 0;
     key.splitk = splits_k(cfg, K) ? 1 : 0;
+    // C is read at all only for beta != 0; the build that requests it ahead of the main loop is
+    // used where a lane has the registers for it (split-K builds leave C to the reduction)
+    key.cpf = (beta != 0.0f && !key.splitk && prefetch_of_c_fits(cfg)) ? 1 : 0;
     if (key.cfg.ns == 0) key.cfg.ns = 2;
     // A vector width is kept only if every access it makes is aligned, and, in a guarded build,
     // if no stored row ends inside a vector (a guarded tile load clamps or zeroes whole vectors).
@@ -410,7 +416,7 @@ int run_config(hipStream_t s, const sgemm_config &cfg, int M, int N, int K, floa
         if (beta == 1.0f) return SGEMM_OK;
         return sgemm_util::launch_scale(s, M, N, beta, C, ldc) == hipSuccess ? SGEMM_OK : SGEMM_E_LAUNCH;
     }
-    const VariantKey key = resolve_variant(cfg, M, N, K, A, lda, B, ldb, C, ldc, layout);
+    const VariantKey key = resolve_variant(cfg, M, N, K, A, lda, B, ldb, C, ldc, layout, beta);
     std::shared_ptr<LoadedKernel> k;
     rc = get_loaded(key, &k);
     if (rc != SGEMM_OK) return rc;
@@ -653,7 +659,7 @@ int sgemm_run_config_padded(void *hip_stream, const sgemm_config *cfg, int M, in
 bool prefers_padding(const sgemm_config &cfg, int M, int N, int K, const float *A, int lda, const float *B,
                      int ldb, const float *C, int ldc, int layout, float alpha, float beta) {
     if (M == 0 || N == 0 || K == 0 || alpha == 0.0f) return false;
-    const VariantKey key = resolve_variant(cfg, M, N, K, A, lda, B, ldb, C, ldc, layout);
+    const VariantKey key = resolve_variant(cfg, M, N, K, A, lda, B, ldb, C, ldc, layout, beta);
     if (!key.edge) return false;
     auto rate_with = [](int wanted, int got) { return wanted < 4 || got >= 4 ? 1.0 : got == 2 ? 0.93 : 0.86; };
     double rate = 1.0;
@@ -678,7 +684,7 @@ static int build_dispatch(int M, int N, int K, float alpha, const float *A, int 
         select_config_locked(M, N, K, layout, &d->chosen);
     }
     d->padded = prefers_padding(d->chosen, M, N, K, A, lda, B, ldb, C, ldc, layout, alpha, beta);
-    const VariantKey key = resolve_variant(d->chosen, M, N, K, A, lda, B, ldb, C, ldc, layout);
+    const VariantKey key = resolve_variant(d->chosen, M, N, K, A, lda, B, ldb, C, ldc, layout, beta);
     const int rc = get_loaded(key, &d->kernel);
     if (rc != SGEMM_OK) return rc;
     const SplitPlan plan = plan_split(key.cfg, K);
@@ -838,7 +844,7 @@ int sgemm_tuned_online(void *hip_stream, int M, int N, int K, float alpha, const
         double ms = -1.0;
         int launched = SGEMM_E_LAUNCH;
         do {
-            const VariantKey key = resolve_variant(cfg, M, N, K, A, lda, B, ldb, C, ldc, layout);
+            const VariantKey key = resolve_variant(cfg, M, N, K, A, lda, B, ldb, C, ldc, layout, beta);
             std::shared_ptr<LoadedKernel> k;
             if (get_loaded(key, &k) != SGEMM_OK) break;
             if (k->info.scratch_bytes > 0 || k->info.lds_bytes > kLdsLimitBytes) break;
@@ -975,33 +981,40 @@ int sgemm_kernel_cache_dir(const char *path) {
     return SGEMM_OK;
 }
 
+// The build that the query functions' `build` flags name.
+static VariantKey named_build(const sgemm_config &cfg, int layout, int build) {
+    VariantKey key{cfg, layout, (build & SGEMM_BUILD_GUARDED) ? 1 : 0, cfg.sk > 1 ? 1 : 0};
+    key.cpf = (build & SGEMM_BUILD_READS_C_AHEAD) && !key.splitk && cfg.mfma ? 1 : 0;
+    return key;
+}
+
 int sgemm_kernel_compile(const sgemm_config *cfg, int layout, int edge, sgemm_kernel_info *info) {
     if (!cfg || layout < 0 || layout > 3) return SGEMM_E_BADARG;
     if (violates_structure(*cfg)) return SGEMM_E_INVALID;
     CodeObject co;
     std::string log;
-    const int rc = get_code_object(VariantKey{*cfg, layout, edge ? 1 : 0, cfg->sk > 1 ? 1 : 0}, &co, &log);
+    const int rc = get_code_object(named_build(*cfg, layout, edge), &co, &log);
     if (rc != SGEMM_OK) set_error(log);
     if (info) *info = co.info;
     return rc;
 }
 
 int sgemm_kernel_resolve(const sgemm_config *cfg, int M, int N, int K, int lda, int ldb, int ldc,
-                         int layout, sgemm_config *variant, int *edge) {
-    if (!cfg || !variant || !edge || M <= 0 || N <= 0 || K <= 0 || layout < 0 || layout > 3) return SGEMM_E_BADARG;
+                         int layout, float beta, sgemm_config *variant, int *build) {
+    if (!cfg || !variant || !build || M <= 0 || N <= 0 || K <= 0 || layout < 0 || layout > 3) return SGEMM_E_BADARG;
     if (violates_structure(*cfg)) return SGEMM_E_INVALID;
     const float *aligned = reinterpret_cast<const float *>(uintptr_t{256}); // stands for any aligned pointer
-    const VariantKey key = resolve_variant(*cfg, M, N, K, aligned, lda, aligned, ldb, aligned, ldc, layout);
+    const VariantKey key = resolve_variant(*cfg, M, N, K, aligned, lda, aligned, ldb, aligned, ldc, layout, beta);
     *variant = key.cfg;
     variant->sk = key.splitk ? std::max(2, cfg->sk) : 1;
-    *edge = key.edge;
+    *build = (key.edge ? SGEMM_BUILD_GUARDED : 0) | (key.cpf ? SGEMM_BUILD_READS_C_AHEAD : 0);
     return SGEMM_OK;
 }
 
 int sgemm_kernel_cache_path(const sgemm_config *cfg, int layout, int edge, char *buf, int cap) {
     if (!cfg || !buf || cap <= 0 || layout < 0 || layout > 3) return SGEMM_E_BADARG;
     if (violates_structure(*cfg)) return SGEMM_E_INVALID;
-    const std::string p = code_object_path(VariantKey{*cfg, layout, edge ? 1 : 0, cfg->sk > 1 ? 1 : 0});
+    const std::string p = code_object_path(named_build(*cfg, layout, edge));
     if ((int)p.size() + 1 > cap) return SGEMM_E_BADARG;
     std::memcpy(buf, p.c_str(), p.size() + 1);
     return SGEMM_OK;
@@ -1009,7 +1022,7 @@ int sgemm_kernel_cache_path(const sgemm_config *cfg, int layout, int edge, char 
 
 int sgemm_kernel_macros(const sgemm_config *cfg, int layout, int edge, char *buf, int cap) {
     if (!cfg || !buf || cap <= 0) return SGEMM_E_BADARG;
-    const std::string m = VariantKey{*cfg, layout, edge ? 1 : 0, cfg->sk > 1 ? 1 : 0}.macros();
+    const std::string m = named_build(*cfg, layout, edge).macros();
     if ((int)m.size() + 1 > cap) return SGEMM_E_BADARG;
     std::memcpy(buf, m.c_str(), m.size() + 1);
     return SGEMM_OK;
@@ -1201,7 +1214,7 @@ int tune_ex(int M, int N, int K, int layout, float alpha, float beta, int strate
         int samples = 0;
         do {
             if (hip_failure) { status = "skipped"; break; }
-            const VariantKey key = resolve_variant(cfg, M, N, K, A, lda, B, ldb, C, ldc, layout);
+            const VariantKey key = resolve_variant(cfg, M, N, K, A, lda, B, ldb, C, ldc, layout, beta);
             std::shared_ptr<LoadedKernel> k;
             std::string log;
             const int rc = load_kernel(key, &k, &log);

@@ -81,6 +81,12 @@ int estimated_registers(const sgemm_config &c) {
 // workgroup's waves on that SIMD: nt / 64 waves on 4 SIMDs.
 static int register_budget(int nt) { return 512 / ((nt + 255) / 256); }
 
+bool prefetch_of_c_fits(const sgemm_config &c) {
+    if (!c.mfma) return false; // the vector-ALU schedule reads C row by row in its epilogue
+    const int mwi = c.mwg / c.mdimc, nwi = c.nwg / c.ndimc;
+    return 2 * mwi * nwi + estimated_registers(c) <= register_budget(threads_of(c));
+}
+
 int direct_loads_per_slab(const sgemm_config &c) {
     const int nt = threads_of(c);
     int ops = 0;

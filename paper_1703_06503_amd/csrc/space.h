@@ -17,6 +17,9 @@ constexpr int kDims = 16;              // tuned fields of sgemm_config, in field
 constexpr int kLdsLimitBytes = 163840; // LDS per workgroup on gfx950
 constexpr int kMaxThreads = 1024;
 constexpr int kMaxSplitK = 64;         // upper bound of the SK parameter
+// Largest leading dimension of A and B (floats): a tile of up to 512 stored rows then spans
+// less than 2 GiB, the reach of the kernels' 32-bit byte offsets and buffer windows.
+constexpr int kMaxLeadingDim = 1 << 20;
 constexpr int kMaxLoadsInFlight = 63;  // the vmcnt counter of a wave
 
 using Point = std::array<int, kDims>;
@@ -30,6 +33,9 @@ int lds_bytes(const sgemm_config &c);       // worst case over the four storage 
 int lds_bytes(const sgemm_config &c, int layout);
 int estimated_registers(const sgemm_config &c); // beside the accumulators
 int direct_loads_per_slab(const sgemm_config &c); // LDS-direct load instructions per thread
+// Whether a lane has registers to hold the old values of its part of C beside its accumulators
+// (builds for beta != 0 then request them before the first slab instead of in the epilogue).
+bool prefetch_of_c_fits(const sgemm_config &c);
 int threads_of(const sgemm_config &c);            // mdimc * ndimc * ksw
 
 // nullptr if c satisfies every constraint, else a short reason.

@@ -11,7 +11,7 @@ import time
 
 
 def _work(args):
-    space, layout, edge, lo, hi, step = args
+    space, layout, edge, lo, hi, step, beta = args
     from . import binding as b
     n_new = n_fail = 0
     for i in range(lo, hi, step):
@@ -20,7 +20,7 @@ def _work(args):
             if isinstance(edge, tuple):     # a problem shape: the build a call of that shape loads
                 M, N, K = edge
                 cfg, e = b.sgemm_kernel_resolve(cfg, M, N, K, M if layout & 1 else K, K if layout & 2 else N,
-                                                N, layout)
+                                                N, layout, beta)
             else:
                 e = edge
             info = b.sgemm_kernel_compile(cfg, layout, e)
@@ -30,7 +30,7 @@ def _work(args):
     return n_new, n_fail
 
 
-def precompile(space=0, layouts=(0,), edges=(0,), jobs=8, indices=None, verbose=True):
+def precompile(space=0, layouts=(0,), edges=(0,), jobs=8, indices=None, verbose=True, beta=0.0):
     from . import binding as b
     n = b.sgemm_space_size(space)
     t0 = time.time()
@@ -45,9 +45,9 @@ def precompile(space=0, layouts=(0,), edges=(0,), jobs=8, indices=None, verbose=
                     indices_now = indices
                 # small strided chunks, so that progress can be reported while the pool works
                 chunks = max(jobs * 8, len(indices_now) // 16)
-                tasks = [(space, layout, edge, j, len(indices_now), chunks) for j in range(chunks)]
+                tasks = [(space, layout, edge, j, len(indices_now), chunks, beta) for j in range(chunks)]
                 if indices is not None:
-                    tasks = [(space, layout, edge, i, i + 1, 1) for i in indices]
+                    tasks = [(space, layout, edge, i, i + 1, 1, beta) for i in indices]
                 last = time.time()
                 for done, r in enumerate(pool.imap_unordered(_work, tasks), 1):
                     total_new += r[0]
@@ -71,6 +71,8 @@ def main(argv=None):
                     help="M,N,K: compile for each configuration the build that a call of this shape "
                          "loads (guarded or not, load vectors narrowed where rows demand it, the "
                          "split-K build where K is split) instead of --edge")
+    ap.add_argument("--beta", type=float, default=0.0,
+                    help="with --shape: the calls' beta (builds for beta != 0 may differ)")
     ap.add_argument("--values", default=None,
                     help='value lists of the caller-defined space (--space 5), e.g. "MWG=64,128 SK=4,8"')
     a = ap.parse_args(argv)
@@ -78,7 +80,7 @@ def main(argv=None):
         import os
         os.environ["SGEMM_TUNED_CUSTOM_SPACE"] = a.values      # the worker processes read it
     edges = [tuple(int(x) for x in a.shape.split(","))] if a.shape else [int(x) for x in a.edge.split(",")]
-    new, fail = precompile(a.space, [int(x) for x in a.layouts.split(",")], edges, a.jobs)
+    new, fail = precompile(a.space, [int(x) for x in a.layouts.split(",")], edges, a.jobs, beta=a.beta)
     print(f"compiled {new} variants, {fail} failed")
     return 1 if fail else 0
 

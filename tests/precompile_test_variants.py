@@ -21,11 +21,16 @@ def _gemm(cfg, layout, edge, extra=""):
     return ("gemm", cfg.as_tuple(), layout, edge, extra)
 
 
-def _resolved(cfg, M, N, K, layout):
-    """The build a call with cfg launches for these sizes (dense operands, aligned pointers)."""
-    lda, ldb = (M if layout & 1 else K), (K if layout & 2 else N)
-    variant, edge = b.sgemm_kernel_resolve(cfg, M, N, K, lda, ldb, N, layout)
-    return _gemm(variant, layout, edge)
+def _resolved(cfg, M, N, K, layout, pad=0):
+    """The builds a call with cfg launches for these sizes (aligned pointers, stored rows `pad`
+    floats longer than the matrices' rows): the one for beta == 0 and the one for beta != 0,
+    which differ for some configurations."""
+    lda, ldb = (M if layout & 1 else K) + pad, (K if layout & 2 else N) + pad
+    out = []
+    for beta in (0.0, 1.0):
+        variant, build = b.sgemm_kernel_resolve(cfg, M, N, K, lda, ldb, N, layout, beta)
+        out.append(_gemm(variant, layout, build))
+    return out
 
 
 def gemm_tasks():
@@ -36,35 +41,42 @@ def gemm_tasks():
     b.sgemm_cache_clear()
     b.sgemm_cache_load(table)
     for M, N, K, layout, _ms, cfg in report.read_table(table):
-        tasks.append(_resolved(b.make_config(*cfg), M, N, K, layout))
+        tasks += _resolved(b.make_config(*cfg), M, N, K, layout)
     # configurations run at the benchmark sizes beside the winners
     for name in ("cfg4_4096", "cfg2_2048", "cfg3_1000", "cfg3_1536"):
         w = synth.WORKLOADS[name]
-        tasks += [_resolved(cfg, w.M, w.N, w.K, w.layout) for cfg in v.BENCH_CONFIGS]
+        tasks += [t for cfg in v.BENCH_CONFIGS for t in _resolved(cfg, w.M, w.N, w.K, w.layout)]
     for name in ("cfg5_128x4096x4096", "cfg5_4096x64x9216"):
         w = synth.WORKLOADS[name]
-        tasks += [_resolved(cfg, w.M, w.N, w.K, w.layout) for cfg in v.SKINNY_CONFIGS]
+        tasks += [t for cfg in v.SKINNY_CONFIGS for t in _resolved(cfg, w.M, w.N, w.K, w.layout)]
     # dispatch without an exactly tuned shape; the pad-and-run path loads the unguarded build
     for M, N, K, layout in v.DISPATCHED_CALLS + [c[:4] for c in v.NOALLOC_CALLS]:
         cfg = b.sgemm_config_select(M, N, K, layout)
-        tasks += [_resolved(cfg, M, N, K, layout), _gemm(cfg, layout, 0)]
+        tasks += _resolved(cfg, M, N, K, layout) + [_gemm(cfg, layout, 0), _gemm(cfg, layout, b.BUILD_READS_C_AHEAD)]
     (M, N, K, layout), cfg = v.NOALLOC_TOO_BIG
-    tasks.append(_resolved(cfg, M, N, K, layout))
+    tasks += _resolved(cfg, M, N, K, layout)
     # the hand-picked configurations, in every layout, guarded and not, and narrowed
     for cfg in v.some_configs():
-        tasks += [_gemm(cfg, layout, edge) for layout in (0, 1, 2, 3) for edge in (0, 1)]
-        tasks += [_resolved(cfg, *v.NARROW_SHAPE, layout) for layout in (0, 3)]
+        tasks += [_gemm(cfg, layout, build) for layout in (0, 1, 2, 3) for build in (0, 1, 2, 3)]
+        tasks += [t for layout in (0, 3) for t in _resolved(cfg, *v.NARROW_SHAPE, layout)]
         for shape in [(97, 83, 45), (130, 70, 33), (1, 1, 1), (5, 300, 2), (200, 100, 300), (150, 140, 60),
                       (192, 160, 192), (384, 256, 512), (300, 200, 150)]:
-            tasks.append(_resolved(cfg, *shape, 0))
+            tasks += _resolved(cfg, *shape, 0)
+    # tests/test_gpu_parity.py: NaN frames around the operands, rows 4 MiB apart
+    for which in (0, 1, 3, 4, 6, 10):
+        for layout in (0, 1, 2, 3):
+            for shape, pad in [((97, 83, 45), 3), ((150, 140, 60), 4), ((64, 64, 64), 8)]:
+                tasks += _resolved(v.some_configs()[which], *shape, layout, pad)
+    for cfg in (v.some_configs()[1], v.some_configs()[4], b.make_config(256, 256, 32, 32, 8, 4, 4, 1, 1, 0, 8, 1, 0, 1, 2)):
+        tasks += _resolved(cfg, 200, 72, 40, 0, (1 << 20) - 72)     # ldb = 2^20; lda is as aligned as 2^20 is
     # the sweeps: which build a case loads depends on the sizes too
     for space, idx, shape, layout in v.all_sweeps():
-        tasks += [_resolved(b.sgemm_space_get(space, i), *shape, layout) for i in idx]
+        tasks += [t for i in idx for t in _resolved(b.sgemm_space_get(space, i), *shape, layout)]
     # the small space: the tuner tests search it on several shapes, once with the planted bug
     for i in range(b.sgemm_space_size(b.SPACE_SMALL)):
         cfg = b.sgemm_space_get(b.SPACE_SMALL, i)
         tasks.append(_gemm(cfg, 0, 0, PLANTED_BUG))
-        tasks += [_resolved(cfg, *shape, 0) for shape in [(192, 160, 96), (256, 256, 128), (320, 256, 192)]]
+        tasks += [t for shape in [(192, 160, 96), (256, 256, 128), (320, 256, 192)] for t in _resolved(cfg, *shape, 0)]
     return tasks
 
 

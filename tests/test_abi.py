@@ -218,6 +218,29 @@ def test_dispatch_pads_only_large_problems_with_rows_that_break_the_load_vector(
     assert b.sgemm_config_prefers_padding(scalar, 4091, 4091, 4091, 4091, 4091, 4091, 0, 0.0) == 0
 
 
+def test_calls_that_read_c_get_the_build_that_requests_it_ahead_where_registers_allow():
+    """beta != 0 on the matrix-core schedule: the build reads the old C before the main loop
+    when a lane can hold it beside its accumulators; never for split-K launches (the reduction
+    reads C), never on the vector-ALU schedule, never for beta == 0."""
+    def build(cfg, M, N, K, beta):
+        return b.sgemm_kernel_resolve(cfg, M, N, K, K, N, N, 0, beta)[1]
+    mid = b.make_config(192, 192, 32, 32, 16, 4, 4, 1, 1, 1, 8, 2, 1, 1, 2)      # 72 accumulators of 256 registers
+    assert build(mid, 3000, 3000, 3000, 1.0) == b.BUILD_GUARDED | b.BUILD_READS_C_AHEAD
+    assert build(mid, 3000, 3000, 3000, 0.0) == b.BUILD_GUARDED
+    assert build(mid, 3072, 3072, 3072, 0.5) == b.BUILD_READS_C_AHEAD
+    big = b.make_config(256, 256, 32, 32, 8, 4, 4, 1, 1, 0, 8, 1, 0, 1, 2)       # 256 accumulators: no room
+    assert build(big, 4096, 4096, 4096, 1.0) == 0
+    split = b.make_config(64, 64, 64, 16, 16, 4, 4, 1, 1, 0, 8, 1, 1, 4, 2)
+    assert build(split, 128, 4096, 4096, 1.0) == 0
+    valu = b.make_config(64, 64, 16, 8, 8, 4, 4, 1, 1, 0, 8, 0, 0, 1, 2)
+    assert build(valu, 1024, 1024, 1024, 1.0) == 0
+    assert "-DCPF=1" in b.sgemm_kernel_macros(mid, 0, b.BUILD_READS_C_AHEAD)
+    assert "-DCPF" not in b.sgemm_kernel_macros(mid, 0, b.BUILD_GUARDED)
+    assert "-DCPF" not in b.sgemm_kernel_macros(valu, 0, b.BUILD_READS_C_AHEAD)
+    paths = {b.sgemm_kernel_cache_path(mid, 0, f) for f in (0, 1, 2, 3)}
+    assert len(paths) == 4                                                      # four builds, four code objects
+
+
 def test_a_tuned_configuration_is_only_lent_to_shapes_like_its_own():
     """Dispatch on a miss: the nearest tuned shape of the same storage layout serves a call only
     when the shapes are alike; otherwise the built-in rule plans tile and split K for the

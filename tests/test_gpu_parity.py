@@ -184,6 +184,51 @@ def test_leading_dimensions_and_untouched_padding(which):
     _check_leading_dimensions(cfg, 97, 83, 45, 48, 84, 84)
 
 
+@pytest.mark.parametrize("layout", [0, 1, 2, 3])
+@pytest.mark.parametrize("which", [0, 1, 3, 4, 6, 10])
+def test_what_lies_beside_the_matrices_is_never_summed(which, layout):
+    """Guarded builds read through windows that end with the matrix and clamp nothing: whatever
+    a lane picks up beyond M, N or K - here NaN in the padding of every stored row and in guard
+    rows behind A and B - must not reach C.  Sizes are ragged in all three dimensions."""
+    import torch
+    cfg = _some_configs()[which]
+    for (M, N, K), pad in [((97, 83, 45), 3), ((150, 140, 60), 4), ((64, 64, 64), 8)]:
+        A, B, C = synth.make_inputs(M, N, K, layout, seed=91 + layout)
+        def framed(X):      # the matrix with `pad` NaN columns on the right and two NaN rows below
+            out = np.full((X.shape[0] + 2, X.shape[1] + pad), np.nan, dtype=np.float32)
+            out[:X.shape[0], :X.shape[1]] = X
+            return out
+        dA, dB, dC = (torch.from_numpy(x).cuda() for x in (framed(A), framed(B), C.copy()))
+        b.sgemm_run_config(None, cfg, M, N, K, 1.5, dA, A.shape[1] + pad, dB, B.shape[1] + pad, 0.25, dC, N, layout)
+        torch.cuda.synchronize()
+        gu.check_against_oracle(dC.cpu().numpy(), A, B, C, 1.5, 0.25, layout, what=f"NaN frame {cfg} {(M, N, K)} layout {layout}")
+
+
+def test_leading_dimensions_up_to_the_documented_limit():
+    """Rows 4 MiB apart (the largest leading dimension the header allows): the kernels' 32-bit
+    offsets reach every row of a tile; one element more is refused."""
+    import torch
+    ld = 1 << 20
+    M, N, K = 200, 72, 40
+    rng = np.random.default_rng(17)
+    A = rng.uniform(-1, 1, (M, K)).astype(np.float32)
+    B = rng.uniform(-1, 1, (K, N)).astype(np.float32)
+    C = rng.uniform(-1, 1, (M, N)).astype(np.float32)
+    dA = torch.zeros((M, ld), dtype=torch.float32, device="cuda")
+    dB = torch.zeros((K, ld), dtype=torch.float32, device="cuda")
+    dA[:, :K] = torch.from_numpy(A).cuda()
+    dB[:, :N] = torch.from_numpy(B).cuda()
+    for cfg in (_some_configs()[1], _some_configs()[4], b.make_config(256, 256, 32, 32, 8, 4, 4, 1, 1, 0, 8, 1, 0, 1, 2)):
+        dC = torch.from_numpy(C.copy()).cuda()
+        b.sgemm_run_config(None, cfg, M, N, K, 1.0, dA, ld, dB, ld, 1.0, dC, N, 0)
+        torch.cuda.synchronize()
+        gu.check_against_oracle(dC.cpu().numpy(), A, B, C, 1.0, 1.0, 0, what=f"ld 2^20 {cfg}")
+        with pytest.raises(b.SgemmError) as e:
+            b.sgemm_run_config(None, cfg, M, N, K, 1.0, dA, ld + 1, dB, ld, 1.0, dC, N, 0)
+        assert e.value.status == b.E_BADARG
+    del dA, dB
+
+
 def _check_leading_dimensions(cfg, M, N, K, lda, ldb, ldc):
     import torch
     rng = np.random.default_rng(53)
