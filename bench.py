@@ -34,21 +34,21 @@ PEAK_FP32_TFLOPS = 157.3   # MI355X published dense FP32 (vector and matrix)
 # so measurements are keyed by workload and (MWG, NWG, GRP, SK); the summaries are under
 # profiles/.  A variant with another tile or order reports null.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/sgemm_tuned_cfg4_4096.txt: 576.59 MiB fetched + 64.00 MiB written (row-major
+    # profiles/sgemm_tuned_cfg4_4096.txt: 576.53 MiB fetched + 64.00 MiB written (row-major
     # tile order: every XCD reads all of A and 2/16 of B)
-    ("cfg4_4096", (256, 256, 0, 1)): (576.59 + 64.00) * 2 ** 20,
+    ("cfg4_4096", (256, 256, 0, 1)): (576.53 + 64.00) * 2 ** 20,
     # XCD-aware order, each XCD a 4 x 8 block of tiles: 384 MiB fetched + 64 MiB written
     ("cfg4_4096", (256, 256, 1, 1)): (196657 * 1.9989 + 65536) * 1024,
     # profiles/sgemm_tuned_cfg1_256.txt, sgemm_tuned_cfg5_*.txt (GEMM launch + plane reduction)
     ("cfg1_256", (32, 32, 0, 1)): (2.28 + 0.25) * 2 ** 20,
-    ("cfg5_128x4096x4096", (64, 64, 1, 4)): (80.02 + 8.00 + 8.03 + 2.00) * 2 ** 20,
+    ("cfg5_128x4096x4096", (64, 64, 0, 4)): (80.01 + 8.00 + 8.03 + 2.00) * 2 ** 20,
     ("cfg5_4096x64x9216", (64, 64, 0, 8)): (161.99 + 8.00 + 8.03 + 1.00) * 2 ** 20,
     # profiles/sgemm_tuned_cfg3_*.txt, cfg2_2048, cfg4_8192
-    ("cfg3_1000", (64, 64, 1, 1)): (27.84 + 3.81) * 2 ** 20,
-    ("cfg3_1536", (96, 96, 1, 1)): (63.10 + 9.00) * 2 ** 20,
-    ("cfg2_2048", (128, 128, 0, 1)): (160.00 + 16.00) * 2 ** 20,
-    ("cfg3_3000", (192, 192, 1, 1)): (244.86 + 34.96) * 2 ** 20,
-    ("cfg4_8192", (256, 256, 0, 1)): (3115.18 + 256.00) * 2 ** 20,
+    ("cfg3_1000", (64, 64, 1, 1)): (28.08 + 3.81) * 2 ** 20,
+    ("cfg3_1536", (96, 96, 1, 1)): (63.11 + 9.00) * 2 ** 20,
+    ("cfg2_2048", (128, 128, 1, 1)): (112.05 + 16.00) * 2 ** 20,
+    ("cfg3_3000", (192, 192, 0, 1)): (357.04 + 34.45) * 2 ** 20,
+    ("cfg4_8192", (256, 256, 1, 1)): (3146.25 + 256.00) * 2 ** 20,
     # the convolution workloads, keyed by the whole configuration: profiles/conv2d_tuned_conv_*.txt
     ("conv_3x3", (64, 8, 4, 1, 0, 1, 0, 1)): (144.02 + 128.00) * 2 ** 20,
     ("conv_7x7", (32, 8, 8, 2, 0, 8, 0, 1)): (144.45 + 128.00) * 2 ** 20,
