@@ -124,6 +124,10 @@ template <int VW> struct reduce_vec;
 template <> struct reduce_vec<1> { typedef float type; };
 template <> struct reduce_vec<4> { typedef float type __attribute__((ext_vector_type(4))); };
 
+// The planes are added in index order (so the result does not depend on timing), but their
+// loads are independent: four at a time are requested before the first of them is added, so an
+// element waits for memory once per four planes instead of once per plane.  The old C, when it
+// is needed, is requested with the first group.
 template <int VW>
 __global__ void splitk_reduce_kernel(int M, int N, int planes, const float *__restrict__ P,
                                      size_t plane, float alpha, float beta, float *__restrict__ C,
@@ -133,13 +137,47 @@ __global__ void splitk_reduce_kernel(int M, int N, int planes, const float *__re
     const size_t n = (size_t)M * nv;
     for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < n;
          e += (size_t)gridDim.x * blockDim.x) {
-        const size_t r = e / nv, c = (e % nv) * VW;
+        size_t r, c;
+        if (n <= 0xffffffffu) { // the usual case: 32-bit division
+            r = (unsigned)e / (unsigned)nv;
+            c = (size_t)((unsigned)e % (unsigned)nv) * VW;
+        } else {
+            r = e / nv;
+            c = (e % nv) * VW;
+        }
         const float *p = P + r * (size_t)N + c;
-        vec acc = *reinterpret_cast<const vec *>(p);
-        for (int s = 1; s < planes; ++s) acc += *reinterpret_cast<const vec *>(p + (size_t)s * plane);
         vec *out = reinterpret_cast<vec *>(C + r * (size_t)ldc + c);
+        vec old = {};
+        if (beta != 0.0f) old = *out; // C is read only when beta != 0
+#define PLANE(i) (*reinterpret_cast<const vec *>(p + (size_t)(i) * plane))
+        vec acc;
+        int s;
+        if (planes >= 8) {
+            const vec v0 = PLANE(0), v1 = PLANE(1), v2 = PLANE(2), v3 = PLANE(3), v4 = PLANE(4), v5 = PLANE(5),
+                      v6 = PLANE(6), v7 = PLANE(7);
+            acc = v0; acc += v1; acc += v2; acc += v3; acc += v4; acc += v5; acc += v6; acc += v7;
+            s = 8;
+        } else if (planes >= 4) {
+            const vec v0 = PLANE(0), v1 = PLANE(1), v2 = PLANE(2), v3 = PLANE(3);
+            acc = v0; acc += v1; acc += v2; acc += v3;
+            s = 4;
+        } else {
+            acc = PLANE(0);
+            s = 1;
+        }
+        for (; s + 4 <= planes; s += 4) {
+            const vec v0 = PLANE(s), v1 = PLANE(s + 1), v2 = PLANE(s + 2), v3 = PLANE(s + 3);
+            acc += v0; acc += v1; acc += v2; acc += v3;
+        }
+        if (s + 2 <= planes) {
+            const vec v0 = PLANE(s), v1 = PLANE(s + 1);
+            acc += v0; acc += v1;
+            s += 2;
+        }
+        if (s < planes) acc += PLANE(s);
+#undef PLANE
         acc = alpha * acc;
-        if (beta != 0.0f) acc += beta * *out; // C is read only when beta != 0
+        if (beta != 0.0f) acc += beta * old;
         *out = acc;
     }
 }
