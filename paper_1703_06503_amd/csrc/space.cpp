@@ -84,7 +84,9 @@ static int register_budget(int nt) { return 512 / ((nt + 255) / 256); }
 bool prefetch_of_c_fits(const sgemm_config &c) {
     if (!c.mfma) return false; // the vector-ALU schedule reads C row by row in its epilogue
     const int mwi = c.mwg / c.mdimc, nwi = c.nwg / c.ndimc;
-    return 2 * mwi * nwi + estimated_registers(c) <= register_budget(threads_of(c));
+    // the old values wait in architected registers, of which a wave addresses 256 (variants of
+    // 64 or 128 threads that pass the test against their whole budget were seen to spill)
+    return 2 * mwi * nwi + estimated_registers(c) <= std::min(register_budget(threads_of(c)), 256);
 }
 
 int direct_loads_per_slab(const sgemm_config &c) {
