@@ -44,7 +44,7 @@ MEASURED_TRAFFIC_BYTES = {
     ("cfg5_128x4096x4096", (64, 64, 0, 4)): (80.01 + 8.00 + 8.03 + 2.00) * 2 ** 20,
     ("cfg5_4096x64x9216", (64, 64, 0, 8)): (161.99 + 8.00 + 8.03 + 1.00) * 2 ** 20,
     # profiles/sgemm_tuned_cfg3_*.txt, cfg2_2048, cfg4_8192
-    ("cfg3_1000", (64, 64, 1, 1)): (28.08 + 3.81) * 2 ** 20,
+    ("cfg3_1000", (64, 64, 1, 1)): (28.06 + 3.81) * 2 ** 20,
     ("cfg3_1536", (96, 96, 1, 1)): (63.09 + 9.00) * 2 ** 20,
     ("cfg2_2048", (128, 128, 1, 1)): (112.05 + 16.00) * 2 ** 20,
     ("cfg3_3000", (192, 192, 0, 1)): (357.04 + 34.45) * 2 ** 20,
