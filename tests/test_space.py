@@ -208,6 +208,33 @@ def test_what_the_register_model_rejects_does_spill():
         assert info.scratch_bytes > 0, (cfg, info.vgprs)
 
 
+def test_builds_that_read_c_ahead_keep_their_registers():
+    """Calls with beta != 0 get the build that requests the old C before the main loop where the
+    library's rule says a lane can hold it (twice the accumulators plus the estimate within the
+    budget and within 256 architected registers).  A seeded sample of matrix-core configurations
+    for which the rule says yes compiles without spills in that build; one it refuses (a single
+    wave with 128 accumulators: fine against the 512 registers of its budget, not against 256)
+    spills when the build is forced."""
+    rng = np.random.default_rng(78)
+    space = [c for c in so.enumerate_space(so.SPACE_MFMA)] + [c for c in so.enumerate_space(so.SPACE_KSPLIT)]
+    chosen, tried = [], 0
+    while len(chosen) < 16 and tried < 400:
+        cfg = space[int(rng.integers(len(space)))]
+        tried += 1
+        M, N, K = 4 * cfg[0], 4 * cfg[1], 8 * cfg[2]
+        variant, build = b.sgemm_kernel_resolve(b.make_config(*cfg), M, N, K, K, N, N, 0, 1.0)
+        if build & b.BUILD_READS_C_AHEAD:
+            chosen.append((cfg, variant, build))
+    assert len(chosen) == 16
+    spilled = [cfg for cfg, variant, build in chosen if b.sgemm_kernel_compile(variant, 0, build).scratch_bytes > 0]
+    assert len(spilled) <= 1, spilled
+    refused = b.make_config(128, 64, 32, 8, 8, 4, 4, 1, 1, 0, 8, 2, 0, 1, 2, 1)
+    assert b.sgemm_config_check(refused) == 0
+    assert b.sgemm_kernel_resolve(refused, 512, 256, 256, 256, 256, 256, 0, 1.0)[1] == 0
+    assert b.sgemm_kernel_compile(refused, 0, 0).scratch_bytes == 0
+    assert b.sgemm_kernel_compile(refused, 0, b.BUILD_READS_C_AHEAD).scratch_bytes > 0
+
+
 def test_loads_in_flight_rule_is_what_the_kernel_itself_asserts():
     """More than two LDS buffers keep the loads of NS - 2 slabs in flight behind the slab that
     is waited for, and the wait is a 6-bit count: the kernel source refuses to compile beyond
