@@ -449,6 +449,7 @@ struct OnlineSearch {
     std::condition_variable cv;
     std::thread worker;
     int wanted = -1;        // configuration the search wants timed next (-1: none yet)
+    bool taken = false;     // a GEMM call has picked `wanted` up and is timing it
     double reported = 0.0;  // its time, once has_report is set
     bool has_report = false;
     bool finished = false;  // the search has ended; best_index holds its result
@@ -467,7 +468,8 @@ struct OnlineSearch {
     }
 };
 std::mutex g_online_mu;
-std::map<std::tuple<int, int, int, int, int>, std::unique_ptr<OnlineSearch>> g_online; // + space
+// (shared: a call keeps its search alive while it waits on it, whoever removes the entry)
+std::map<std::tuple<int, int, int, int, int>, std::shared_ptr<OnlineSearch>> g_online; // + space
 
 } // namespace
 
@@ -800,18 +802,19 @@ int sgemm_tuned_online(void *hip_stream, int M, int N, int K, float alpha, const
     if (tuned || M == 0 || N == 0 || K == 0 || alpha == 0.0f || budget <= 0)
         return sgemm_tuned_on(hip_stream, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, layout);
 
-    OnlineSearch *os;
+    std::shared_ptr<OnlineSearch> os;
     {
         std::lock_guard<std::mutex> lock(g_online_mu);
         auto &slot = g_online[std::make_tuple(M, N, K, layout, space_id)];
         if (!slot) {
-            slot.reset(new OnlineSearch);
+            slot = std::make_shared<OnlineSearch>();
             OnlineSearch *self = slot.get();
             const uint64_t seed = ((uint64_t)M * 1000003ull + (uint64_t)N) * 1000003ull + (uint64_t)K + (uint64_t)layout;
             self->worker = std::thread([self, space, strategy, budget, seed] {
                 const SearchResult r = run_search(*space, strategy, budget, seed, StrategyParams{}, [self](int idx) {
                     std::unique_lock<std::mutex> lock(self->mu);
                     self->wanted = idx;
+                    self->taken = false;
                     self->has_report = false;
                     self->cv.notify_all();
                     self->cv.wait(lock, [self] { return self->has_report || self->abandoned; });
@@ -826,7 +829,7 @@ int sgemm_tuned_online(void *hip_stream, int M, int N, int K, float alpha, const
                 self->cv.notify_all();
             });
         }
-        os = slot.get();
+        os = slot;
     }
 
     // One GEMM per call, done by the next candidate that compiles and launches; a candidate
@@ -836,9 +839,11 @@ int sgemm_tuned_online(void *hip_stream, int M, int N, int K, float alpha, const
         int idx;
         {
             std::unique_lock<std::mutex> lock(os->mu);
-            os->cv.wait(lock, [os] { return os->finished || (os->wanted >= 0 && !os->has_report); });
+            // one call per candidate: concurrent calls of the same shape wait for the next one
+            os->cv.wait(lock, [&os] { return os->finished || (os->wanted >= 0 && !os->has_report && !os->taken); });
             if (os->finished) break;
             idx = os->wanted;
+            os->taken = true;
         }
         const sgemm_config cfg = from_point(space->configs[idx]);
         double ms = -1.0;
@@ -881,7 +886,8 @@ int sgemm_tuned_online(void *hip_stream, int M, int N, int K, float alpha, const
     }
     {
         std::lock_guard<std::mutex> lock(g_online_mu);
-        g_online.erase(std::make_tuple(M, N, K, layout, space_id));
+        auto it = g_online.find(std::make_tuple(M, N, K, layout, space_id));
+        if (it != g_online.end() && it->second == os) g_online.erase(it);
     }
     return sgemm_tuned_on(hip_stream, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, layout);
 }
@@ -1161,6 +1167,7 @@ int tune_ex(int M, int N, int K, int layout, float alpha, float beta, int strate
         A = opts->A; B = opts->B; C = opts->C; C0 = opts->C0;
         lda = opts->lda; ldb = opts->ldb; ldc = opts->ldc;
         if (lda < a_cols || ldb < b_cols || ldc < N) return SGEMM_E_BADARG;
+        if (lda > kMaxLeadingDim || ldb > kMaxLeadingDim) return SGEMM_E_BADARG; // as in every GEMM call
         if (beta != 0.0f && !C0) return SGEMM_E_BADARG;
     } else {
         lda = a_cols; ldb = b_cols; ldc = N;

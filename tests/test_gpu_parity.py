@@ -609,6 +609,50 @@ def test_online_tuning_settles_on_a_configuration_and_every_call_is_correct(stra
         _restore_cache()
 
 
+def test_online_tuning_with_concurrent_callers_of_one_shape():
+    """Several host threads make their first calls of the same shape at once: each candidate of
+    the search is handed to exactly one of them, every call still computes its own GEMM, and the
+    threads that are still waiting when the search ends are served by the winner."""
+    import threading
+    import torch
+    M, N, K = 320, 256, 192
+    A, B, C = synth.make_inputs(M, N, K, 0, seed=75)
+    dA, dB, dC0 = (torch.from_numpy(x).cuda() for x in (A, B, C))
+    ref = orc.sgemm(1.25, A, B, 0.5, C, 0)
+    torch.cuda.synchronize()
+    b.sgemm_cache_clear()
+    failures = []
+
+    def caller(who):
+        try:
+            torch.cuda.set_device(0)
+            dC = dC0.clone()
+            for call in range(10):
+                dC.copy_(dC0)
+                torch.cuda.synchronize()
+                b.sgemm_tuned_online(None, M, N, K, 1.25, dA, K, dB, N, 0.5, dC, N, 0,
+                                     space=b.SPACE_SMALL, strategy=b.STRATEGY_FULL, budget=1)
+                torch.cuda.synchronize()
+                gu.check_against_oracle(dC.cpu().numpy(), A, B, C, 1.25, 0.5, 0, ref,
+                                        what=f"thread {who} call {call}")
+        except BaseException as e:  # noqa: BLE001 - reported by the test's own thread below
+            failures.append((who, repr(e)))
+
+    try:
+        threads = [threading.Thread(target=caller, args=(i,)) for i in range(3)]
+        for t in threads:
+            t.start()
+        for t in threads:
+            t.join(120)
+        assert not any(t.is_alive() for t in threads), "a caller never returned"
+        assert not failures, failures
+        # 30 calls for 16 candidates: the search has ended and its winner is in the table
+        winner = b.sgemm_config_get(M, N, K, 0)
+        assert winner is not None and b.sgemm_space_find(b.SPACE_SMALL, winner) >= 0
+    finally:
+        _restore_cache()
+
+
 def test_launch_on_a_side_stream_and_on_the_set_stream():
     import torch
     cfg = _some_configs()[1]
