@@ -225,7 +225,10 @@ int sgemm_tuned_noalloc(void *hip_stream, int M, int N, int K, float alpha, cons
  * returns a correct C.  A configuration that fails to compile, spills or fails to launch counts
  * as evaluated and the same call goes on to the next one.  Candidates are timed once, cold, and
  * are not re-verified against the reference kernel: a quick, noisy search compared with tune().
- * Calls for one shape must not overlap in time while it is being tuned. */
+ * Host threads may make calls of one shape at the same time while it is being tuned: each
+ * candidate is handed to exactly one call, the others wait for the next one (or for the end of
+ * the search) and every call still computes its own GEMM; the times measured then include
+ * whatever else the device was doing, as with any concurrent use. */
 int sgemm_tuned_online(void *hip_stream, int M, int N, int K, float alpha, const float *A, int lda,
                        const float *B, int ldb, float beta, float *C, int ldc, int layout,
                        int space, int strategy, int budget);
