@@ -42,3 +42,24 @@ def test_strategy_study_accepts_the_convolution_spaces():
     opt, rows = ss.study(table, replay, 20, 4)
     assert opt == 1.0 and len(rows) == 6
     assert all(0 < r["mean_pct_of_best"] <= 100.0 for r in rows)
+
+
+def test_recorded_full_searches_cover_their_spaces():
+    """The committed tables of the two recorded GEMM full searches hold one row per
+    configuration of the space they name, and the optimum that the studies are measured against
+    is the configuration their write-ups name."""
+    import os
+    import numpy as np
+    from paper_1703_06503_amd import binding as b
+    from paper_1703_06503_amd import strategy_study as ss
+    results = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "results")
+    for name, space, tile in [("full_search_cfg2_2048.csv", "full", (128, 64, 32)),
+                              ("full_search_cfg4_4096_mfma.csv", "mfma", (256, 256, 32))]:
+        n, _ = ss.space_size_and_replay(space)
+        with open(os.path.join(results, name)) as f:
+            assert sum(1 for _ in f) == n + 1                       # header + one row each
+        table = ss.load_table(os.path.join(results, name), n)
+        timed = table > 0
+        assert timed.sum() >= 0.99 * n                              # the rest spilled registers
+        best = b.sgemm_space_get(ss.SPACES[space], int(np.argmin(np.where(timed, table, np.inf))))
+        assert (best.mwg, best.nwg, best.kwg) == tile
