@@ -101,7 +101,8 @@ def register_estimate(cfg):
     fragments (the block being multiplied and the one fetched ahead), the registers that stage
     the next slab on its way from global memory to LDS, two address registers per global load
     instruction of a slab, and 24 for loop state, tile origin and the epilogue.  The last two
-    terms are fitted to what the compiler reports ("register model")."""
+    terms are fitted to what the compiler reports for sampled variants of every preset, under
+    the condition that no configuration close to a measured optimum is rejected."""
     MWG, NWG, KWG, MDIMC, NDIMC, VWM, VWN, SA, SB, _, KWI, MFMA = cfg[:12]
     threads = MDIMC * NDIMC * (cfg[15] if len(cfg) > 15 else 1)
     MWI, NWI = MWG // MDIMC, NWG // NDIMC
