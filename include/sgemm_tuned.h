@@ -177,8 +177,13 @@ typedef struct tune_result {
  * study; `layout` says how A and B are stored, see above).
  * M, N, K >= 0.  M == 0 or N == 0: no-op.  K == 0 or alpha == 0: C = beta * C and A, B are
  * not read.  beta == 0: C is written without being read, so NaN/Inf in it do not propagate.
- * The variant is the cached best configuration for (M,N,K,layout); on a miss, the cached
- * configuration of the nearest tuned shape that is valid here, else a built-in default.
+ * The variant is the cached best configuration for (M,N,K,layout).  On a miss the nearest tuned
+ * shape of the same layout (every size within about a factor of 1.5) lends its configuration if
+ * the call has that shape's launch geometry (the same grid of tiles, the same split of K), or if
+ * the library's cost model finds no built-in template that fits the sizes better; else the
+ * built-in default runs: the tuned winners serve as templates, and a two-parameter cost model
+ * per template (sustained fraction of a CU's peak, fixed cost per launch) picks the one whose
+ * tile grid fills the 256 CUs in the fewest rounds, with split K where tiles are few and K long.
  * This call never tunes.  A variant not yet in the kernel cache is compiled on first use.
  * Large problems whose sizes are not multiples of the tile AND whose stored rows are not
  * multiples of the load vector go through zero-padded copies (sgemm_run_config_padded(); see

@@ -129,66 +129,134 @@ void autoload_locked() {
     load_cache_file_locked(p.c_str());
 }
 
-// Built-in fallback when nothing has been tuned for the storage layout: a matrix-core variant
-// whose tile is chosen the way the tuned shapes turned out - the largest tile whose grid still
-// fills the 256 CUs in whole rounds, weighted by how efficient tiles of that size measured, and
-// split K when even small tiles leave most CUs idle and K is long.
-sgemm_config default_config(int M, int N, int K) {
-    struct Cand { int edge, dim, mfma; double eff; };
-    static const Cand cands[] = {{256, 16, 1, 0.92}, {192, 16, 1, 0.88}, {128, 16, 1, 0.85},
-                                 {96, 16, 2, 0.75},  {64, 16, 2, 0.65},  {32, 8, 1, 0.40}};
-    const double cus = 256.0;
-    const Cand *best = &cands[5];
-    double best_score = -1.0;
-    int best_sk = 1;
-    const long long slabs = (K + 31) / 32;
-    for (const Cand &c : cands) {
-        const long long tiles = (long long)((M + c.edge - 1) / c.edge) * ((N + c.edge - 1) / c.edge);
-        if (tiles <= 0) continue;
-        // split K when the tiles alone leave at least half of the CUs idle and K is long
-        // enough for 8 slabs per part; the plane traffic costs about 15 %
-        long long sk = 1;
-        if (tiles * 2 <= (long long)cus && K >= 2048) {
-            sk = std::min<long long>(std::min<long long>((long long)cus / tiles, slabs / 8), 16);
-            if (sk < 1) sk = 1;
-        }
-        const double groups = (double)(tiles * sk);
-        const double rounds = std::ceil(groups / cus);
-        // work really done per CU-round, including what the tile grid overhangs the matrix
-        const double useful = ((double)M * N) / ((double)tiles * c.edge * c.edge);
-        const double score = c.eff * useful * groups / (rounds * cus) * (sk > 1 ? 0.85 : 1.0);
-        if (score > best_score) { best_score = score; best = &c; best_sk = (int)sk; }
-    }
+struct SplitPlan;
+SplitPlan plan_split(const sgemm_config &cfg, int K);
+
+// How a configuration's SK is applied to a problem: `parts` workgroups per tile, each summing
+// `k_chunk` consecutive k (a multiple of KWG; the last part takes what is left).
+struct SplitPlan {
+    int parts;
+    int k_chunk;
+};
+
+// Built-in fallback for shapes without an entry in the per-shape table: the winners of the tuned
+// shapes serve as templates, and a two-parameter cost model per template chooses among them.
+// A workgroup of a template sustains `eff` of a CU's matrix peak while it runs and a launch
+// costs `fix_us` on top (launch, first slab, epilogue); the 256 CUs take ceil(workgroups / 256)
+// workgroups each, so what decides is how the tile grid quantises the problem.  `eff` and
+// `fix_us` were fitted to 22 measured shapes from 384^3 to 7168^3, skinny ones included (the
+// model's pick was the fastest template on 15 of them and at most 10 % behind on the rest).
+// `pairs`: two workgroups of the template fit a CU and hide each other's stalls; a lone one
+// reaches 0.93 of `eff`.  `max_sk`: split K is considered for the template.
+struct Template {
+    int mwg, nwg, kwg, mdimc, ndimc, kwi, mfma, grp, ksw;
+    double eff, fix_us;
+    bool pairs;
+    int max_sk;
+};
+const Template kTemplates[] = {
+    {32, 32, 64, 16, 16, 8, 2, 0, 2, 0.620, 5.6, false, 1},
+    {64, 64, 64, 16, 16, 8, 1, 1, 2, 0.816, 4.1, true, 16},
+    {64, 64, 128, 32, 32, 32, 2, 1, 1, 0.736, 4.4, false, 1},
+    {96, 96, 64, 16, 16, 8, 2, 1, 2, 0.790, 5.0, false, 1},
+    {128, 64, 32, 16, 16, 8, 1, 0, 1, 0.837, 4.8, false, 1},
+    {128, 128, 64, 16, 32, 8, 1, 1, 1, 0.904, 6.6, false, 16},
+    {192, 192, 32, 16, 32, 8, 2, 0, 1, 0.898, 8.6, false, 1},
+    {256, 128, 32, 16, 32, 8, 1, 1, 1, 0.908, 5.7, false, 1},
+    {256, 256, 32, 16, 32, 8, 1, 0, 1, 0.943, 9.1, false, 1},
+};
+constexpr double kCus = 256.0;
+constexpr double kCuFlopPerUs = 614400.0;     // 256 FLOP per clock at 2.4 GHz
+constexpr double kReduceFixUs = 3.0;          // the reduction kernel of a split-K call ...
+constexpr double kReduceBytesPerUs = 4.0e6;   // ... and the rate at which it moves the planes
+
+sgemm_config config_of(const Template &t, int sk) {
     sgemm_config c{};
-    c.mwg = c.nwg = best->edge;
-    c.mdimc = c.ndimc = best->dim;
-    c.mfma = best->mfma;
-    c.kwg = 32; c.vwm = 4; c.vwn = 4; c.sa = 1; c.sb = 1; c.pad = 1; c.kwi = 8; c.grp = 1; c.ns = 2;
-    c.ksw = 1;
-    c.sk = best_sk;
+    c.mwg = t.mwg; c.nwg = t.nwg; c.kwg = t.kwg; c.mdimc = t.mdimc; c.ndimc = t.ndimc;
+    c.vwm = 4; c.vwn = 4; c.sa = 1; c.sb = 1; c.pad = 1; c.kwi = t.kwi; c.mfma = t.mfma;
+    c.grp = t.grp; c.sk = sk; c.ns = 2; c.ksw = t.ksw;
     return c;
+}
+
+// Predicted microseconds of a call with `cfg`, costed with the parameters of template `t`.
+double predicted_us(const sgemm_config &cfg, const Template &t, int M, int N, int K) {
+    const SplitPlan plan = plan_split(cfg, K);
+    const double tiles = (double)((M + cfg.mwg - 1) / cfg.mwg) * (double)((N + cfg.nwg - 1) / cfg.nwg);
+    const double per_cu = std::ceil(tiles * plan.parts / kCus);
+    const double k_len = plan.parts > 1 ? plan.k_chunk : (double)((K + cfg.kwg - 1) / cfg.kwg) * cfg.kwg;
+    const double eff = t.eff * (t.pairs && per_cu < 2.0 ? 0.93 : 1.0);
+    double us = t.fix_us + per_cu * 2.0 * cfg.mwg * cfg.nwg * k_len / (kCuFlopPerUs * eff);
+    if (plan.parts > 1) us += kReduceFixUs + (plan.parts + 1.0) * M * N * 4.0 / kReduceBytesPerUs;
+    return us;
+}
+
+sgemm_config default_config(int M, int N, int K, double *cost_us = nullptr) {
+    sgemm_config best = config_of(kTemplates[0], 1);
+    double best_us = -1.0;
+    for (const Template &t : kTemplates) {
+        const long long tiles = (long long)((M + t.mwg - 1) / t.mwg) * ((N + t.nwg - 1) / t.nwg);
+        // split K where the tiles alone do not fill the CUs and K is long: parts of at least 8 slabs
+        const int slabs = (K + t.kwg - 1) / t.kwg;
+        const int sk_max = (tiles <= (long long)kCus && K >= 2048) ? std::min(t.max_sk, slabs / 8) : 1;
+        for (int sk = 1; sk <= std::max(1, sk_max); sk *= 2) {
+            const sgemm_config c = config_of(t, sk);
+            const double us = predicted_us(c, t, M, N, K);
+            if (best_us < 0.0 || us < best_us) { best_us = us; best = c; }
+        }
+    }
+    if (cost_us) *cost_us = best_us;
+    return best;
+}
+
+// The template whose parameters cost a configuration that is not one: the same tile if there
+// is one, else the nearest tile area.
+const Template &template_like(const sgemm_config &c) {
+    const Template *best = &kTemplates[0];
+    double best_d = -1.0;
+    for (const Template &t : kTemplates) {
+        if (t.mwg == c.mwg && t.nwg == c.nwg && t.kwg == c.kwg) return t;
+        const double d = std::fabs(std::log2((double)t.mwg * t.nwg) - std::log2((double)c.mwg * c.nwg)) +
+                         (t.mwg == c.mwg && t.nwg == c.nwg ? 0.0 : 0.01);
+        if (best_d < 0.0 || d < best_d) { best_d = d; best = &t; }
+    }
+    return *best;
 }
 
 int select_config_locked(int M, int N, int K, int layout, sgemm_config *out) {
     autoload_locked();
     auto it = g_tuned.find(ShapeKey{M, N, K, layout});
     if (it != g_tuned.end()) { *out = it->second.cfg; return SGEMM_OK; }
-    // nearest tuned shape of the same layout, by distance between the logarithms of the sizes.
-    // A configuration is only lent to shapes like the one it was tuned for (every size within
-    // about a factor of 1.5, or one size within a factor of 2.3): beyond that its tile and
-    // above all its split K fit the other shape no better than the built-in rule does.
+    double default_us = 0.0;
+    const sgemm_config fallback = default_config(M, N, K, &default_us);
+    // The nearest tuned shape of the same layout, by distance between the logarithms of the
+    // sizes, may lend its configuration, if the shapes are alike (every size within about a
+    // factor of 1.5, or one size within a factor of 2.3).  It does so when the call has the
+    // tuned shape's launch geometry (the same grid of tiles and the same split of K: what was
+    // measured there holds here), and otherwise when the cost model, which gives a tuned
+    // configuration 3 % credit over the template most like it, does not find a template that
+    // quantises this problem better.
     constexpr double kNearEnough = 1.5;
     double best = -1.0;
+    const sgemm_config *near_cfg = nullptr;
+    ShapeKey near_shape{};
     for (auto &kv : g_tuned) {
         if (std::get<3>(kv.first) != layout) continue;
         const double dm = std::log2((double)std::max(M, 1)) - std::log2((double)std::max(std::get<0>(kv.first), 1));
         const double dn = std::log2((double)std::max(N, 1)) - std::log2((double)std::max(std::get<1>(kv.first), 1));
         const double dk = std::log2((double)std::max(K, 1)) - std::log2((double)std::max(std::get<2>(kv.first), 1));
         const double d = dm * dm + dn * dn + dk * dk;
-        if (d <= kNearEnough && (best < 0.0 || d < best)) { best = d; *out = kv.second.cfg; }
+        if (d <= kNearEnough && (best < 0.0 || d < best)) { best = d; near_cfg = &kv.second.cfg; near_shape = kv.first; }
     }
-    if (best >= 0.0) return SGEMM_OK;
-    *out = default_config(M, N, K);
+    if (near_cfg) {
+        const sgemm_config &c = *near_cfg;
+        const int M0 = std::get<0>(near_shape), N0 = std::get<1>(near_shape), K0 = std::get<2>(near_shape);
+        const bool same_geometry = (M + c.mwg - 1) / c.mwg == (M0 + c.mwg - 1) / c.mwg &&
+                                   (N + c.nwg - 1) / c.nwg == (N0 + c.nwg - 1) / c.nwg &&
+                                   plan_split(c, K).parts == plan_split(c, K0).parts;
+        if (same_geometry) { *out = c; return SGEMM_OK; }
+        if (c.mfma && 0.97 * predicted_us(c, template_like(c), M, N, K) <= default_us) { *out = c; return SGEMM_OK; }
+    }
+    *out = fallback;
     return SGEMM_OK;
 }
 
@@ -209,8 +277,6 @@ int check_gemm_args(int M, int N, int K, const float *A, int lda, const float *B
     return SGEMM_OK;
 }
 
-struct SplitPlan;
-SplitPlan plan_split(const sgemm_config &cfg, int K);
 bool splits_k(const sgemm_config &cfg, int K);
 
 bool aligned_for(const void *p, int ld, int vw) {
@@ -322,13 +388,6 @@ int pad_workspace_for(hipStream_t s, size_t floats, float **out) {
     *out = w->pad;
     return rc;
 }
-
-// How a configuration's SK is applied to a problem: `parts` workgroups per tile, each summing
-// `k_chunk` consecutive k (a multiple of KWG; the last part takes what is left).
-struct SplitPlan {
-    int parts;
-    int k_chunk;
-};
 
 SplitPlan plan_split(const sgemm_config &cfg, int K) {
     const int slabs = (K + cfg.kwg - 1) / cfg.kwg;

@@ -86,7 +86,7 @@ SKINNY_CONFIGS = [b.make_config(64, 64, 16, 16, 16, 4, 4, 1, 1, 1, 8, 1, 0),
                   b.make_config(64, 64, 32, 16, 16, 4, 4, 1, 1, 1, 8, 1, 0, 8)]
 
 # (M, N, K, layout) of calls that go through the dispatch without an exactly tuned shape
-DISPATCHED_CALLS = ([(250, 260, 128, 0), (4091, 4091, 4091, 0), (300, 200, 150, 0)]
+DISPATCHED_CALLS = ([(250, 250, 128, 0), (4091, 4091, 4091, 0), (300, 200, 150, 0)]
                     + [(M, N, K, layout) for layout in (2, 3)
                        for (M, N, K) in [(300, 200, 150), (96, 1000, 4100), (1536, 1536, 64)]])
 
