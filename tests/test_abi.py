@@ -151,9 +151,17 @@ def test_default_configuration_is_valid_and_sized_to_the_problem():
     assert b.sgemm_config_default(4096, 4096, 4096).mwg == 256
     assert b.sgemm_config_default(3000, 3000, 3000).mwg == 192        # 16 x 16 tiles
     assert b.sgemm_config_default(1536, 1536, 1536).mwg == 96         # 16 x 16 tiles
-    # few tiles and a long K: split K
+    # the tile is chosen for how its grid quantises the problem, not for its size: 6144 = 48 x 128
+    # gives nine whole rounds of 256 workgroups where the 256-wide tile would run 2.25 (three)
+    c = b.sgemm_config_default(6144, 6144, 6144)
+    assert (c.mwg, c.nwg) == (128, 128) and (6144 // 128) ** 2 % 256 == 0
+    assert b.sgemm_config_default(5120, 5120, 5120).mwg == 192        # 27 x 27 tiles: 2.85 rounds
+    assert b.sgemm_config_default(512, 512, 512).mwg == 32            # 256 tiles of 32 x 32
+    # few tiles and a long K: split K, into parts that put two workgroups on every CU
     assert b.sgemm_config_default(128, 4096, 4096).sk > 1
     assert b.sgemm_config_default(128, 4096, 64).sk == 1
+    c = b.sgemm_config_default(64, 8192, 8192)
+    assert (c.mwg, c.nwg, c.sk) == (64, 64, 4)                        # 128 tiles x 4 parts = 2 x 256
 
 
 def test_per_shape_cache_roundtrip(tmp_path):
