@@ -53,8 +53,10 @@ def _pow2(v):
 
 
 def tile_edge_ok(v):
-    """A tile edge is 2^a or 3 * 2^a, between 8 and 512."""
-    return 8 <= v <= 512 and (_pow2(v) or (v % 3 == 0 and _pow2(v // 3)))
+    """A tile edge is 2^a, 3 * 2^a, 5 * 2^a or 7 * 2^a, between 8 and 512: the odd factors are
+    there so that a grid of equal tiles can fill the 256 CUs in whole rounds for sizes that
+    powers of two quantise badly (3000 = 15.6 x 192, 2560 = 16 x 160, 3584 = 16 x 224)."""
+    return 8 <= v <= 512 and any(v % f == 0 and _pow2(v // f) for f in (1, 3, 5, 7))
 
 
 def lds_bytes(cfg, layout):
