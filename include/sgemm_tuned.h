@@ -84,7 +84,7 @@ extern "C" {
  * staging per operand, and the unroll factor Kwi of the Kwg loop.  `pad`, `mfma`, `grp`,
  * `sk`, `ns` and `ksw` are gfx950 additions.  All fields are plain ints so the struct is an int[16]. */
 typedef struct sgemm_config {
-    int mwg, nwg, kwg; /* workgroup macro-tile of C (mwg x nwg: each 2^a or 3*2^a) and K slab
+    int mwg, nwg, kwg; /* workgroup macro-tile of C (mwg x nwg: each 2^a, 3*2^a, 5*2^a or 7*2^a) and K slab
                           per step (power of two)                                          */
     int mdimc, ndimc;  /* threads per workgroup = mdimc * ndimc (multiple of 64), times ksw */
     int vwm;           /* floats per global load of A (1, 2, 4)                          */

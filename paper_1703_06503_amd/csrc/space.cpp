@@ -50,12 +50,14 @@ int lds_bytes(const sgemm_config &c) {
 
 static bool is_pow2_between(int v, int lo, int hi) { return v >= lo && v <= hi && (v & (v - 1)) == 0; }
 
-// Tile edges are 2^a or 3 * 2^a: the second family (96, 192, ...) lets the tile grid fit sizes
-// that powers of two quantise badly (3000 = 15.6 x 192, 1536 = 16 x 96).
+// Tile edges are 2^a, 3 * 2^a, 5 * 2^a or 7 * 2^a: the odd factors (96, 192; 80, 160; 112, 224)
+// let the tile grid fit sizes that powers of two quantise badly (3000 = 15.6 x 192,
+// 1536 = 16 x 96, 2560 = 16 x 160, 3584 = 16 x 224).
 static bool is_tile_edge(int v, int lo, int hi) {
     if (v < lo || v > hi) return false;
-    if ((v & (v - 1)) == 0) return true;
-    return v % 3 == 0 && ((v / 3) & (v / 3 - 1)) == 0;
+    for (int f : {1, 3, 5, 7})
+        if (v % f == 0 && ((v / f) & (v / f - 1)) == 0) return true;
+    return false;
 }
 
 // Registers a lane needs beside its accumulators: two KWI blocks of operand fragments (the one

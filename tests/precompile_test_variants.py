@@ -69,6 +69,8 @@ def gemm_tasks():
                 tasks += _resolved(v.some_configs()[which], *shape, layout, pad)
     for cfg in (v.some_configs()[1], v.some_configs()[4], b.make_config(256, 256, 32, 32, 8, 4, 4, 1, 1, 0, 8, 1, 0, 1, 2)):
         tasks += _resolved(cfg, 200, 72, 40, 0, (1 << 20) - 72)     # ldb = 2^20; lda is as aligned as 2^20 is
+    for cfg in v.ODD_EDGE_CONFIGS:
+        tasks += [t for shape in v.ODD_EDGE_SHAPES for layout in (0, 1, 2, 3) for t in _resolved(cfg, *shape, layout)]
     # the sweeps: which build a case loads depends on the sizes too
     for space, idx, shape, layout in v.all_sweeps():
         tasks += [t for i in idx for t in _resolved(b.sgemm_space_get(space, i), *shape, layout)]

@@ -155,7 +155,8 @@ def test_default_configuration_is_valid_and_sized_to_the_problem():
     # gives nine whole rounds of 256 workgroups where the 256-wide tile would run 2.25 (three)
     c = b.sgemm_config_default(6144, 6144, 6144)
     assert (c.mwg, c.nwg) == (128, 128) and (6144 // 128) ** 2 % 256 == 0
-    assert b.sgemm_config_default(5120, 5120, 5120).mwg == 192        # 27 x 27 tiles: 2.85 rounds
+    assert b.sgemm_config_default(5120, 5120, 5120).mwg == 160        # 32 x 32 tiles: four whole rounds
+    assert b.sgemm_config_default(3584, 3584, 3584).mwg == 224        # 16 x 16 tiles
     assert b.sgemm_config_default(512, 512, 512).mwg == 32            # 256 tiles of 32 x 32
     # few tiles and a long K: split K, into parts that put two workgroups on every CU
     assert b.sgemm_config_default(128, 4096, 4096).sk > 1

@@ -117,6 +117,31 @@ def test_transposed_storage(layout):
 WHICH = list(range(12))
 
 
+@pytest.mark.parametrize("layout", [0, 1, 2, 3])
+def test_tile_edges_of_five_and_seven_times_a_power_of_two(layout):
+    """Tiles of 160, 224, 80 x 112 and 112 x 80: on a shape that all of them divide and on a
+    ragged one, beta != 0, every storage layout."""
+    from tests.variants import ODD_EDGE_CONFIGS, ODD_EDGE_SHAPES
+    for shape in ODD_EDGE_SHAPES:
+        A, B, C = synth.make_inputs(*shape, layout, seed=61 + layout)
+        ref = orc.sgemm(0.75, A, B, -1.25, C, layout)
+        for cfg in ODD_EDGE_CONFIGS:
+            print(f"case {cfg} shape={shape} layout={layout}", flush=True)
+            got = gu.run_gpu(cfg, A, B, C, 0.75, -1.25, layout)
+            gu.check_against_oracle(got, A, B, C, 0.75, -1.25, layout, ref, what=f"{cfg} {shape} layout {layout}")
+
+
+def test_dispatch_picks_odd_tile_edges_where_they_fill_the_cus():
+    """2560 = 16 x 160 and 3584 = 16 x 224: the built-in rule takes those tiles (no entry in the
+    table is near enough in K), and the calls are right."""
+    for (M, N, K, layout), edge in [((2560, 2560, 1536, 0), 160), ((3584, 3584, 1024, 3), 224)]:
+        cfg = b.sgemm_config_select(M, N, K, layout)
+        assert (cfg.mwg, cfg.nwg) == (edge, edge), cfg
+        A, B, C = synth.make_inputs(M, N, K, layout, seed=62)
+        got = gu.run_gpu(None, A, B, C, 1.0, 0.5, layout, entry="tuned")
+        gu.check_against_oracle(got, A, B, C, 1.0, 0.5, layout, what=f"{(M, N, K)} layout {layout} {cfg}")
+
+
 @pytest.mark.parametrize("which", WHICH)
 def test_integer_inputs_are_bit_exact(which):
     """Small-integer operands: every summation order gives the same float, so the GPU must

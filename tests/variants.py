@@ -85,8 +85,16 @@ BENCH_CONFIGS = [
 SKINNY_CONFIGS = [b.make_config(64, 64, 16, 16, 16, 4, 4, 1, 1, 1, 8, 1, 0),
                   b.make_config(64, 64, 32, 16, 16, 4, 4, 1, 1, 1, 8, 1, 0, 8)]
 
+# tile edges of 5 and 7 times a power of two (the built-in templates for sizes like 2560 and 3584 use
+# them): the two templates, a mixed tile with wave groups and split K, and one with unpadded LDS rows
+ODD_EDGE_CONFIGS = [b.make_config(160, 160, 32, 16, 16, 4, 4, 1, 1, 1, 8, 2, 1),
+                    b.make_config(224, 224, 32, 16, 16, 4, 4, 1, 1, 1, 8, 2, 1),
+                    b.make_config(80, 112, 64, 8, 8, 4, 4, 1, 1, 1, 8, 2, 0, 2, 2, 4),
+                    b.make_config(112, 80, 64, 8, 8, 4, 4, 1, 1, 0, 8, 2, 1, 1, 2, 2)]
+ODD_EDGE_SHAPES = [(1120, 1120, 128), (333, 500, 200)]     # a multiple of every such tile, and a ragged one
+
 # (M, N, K, layout) of calls that go through the dispatch without an exactly tuned shape
-DISPATCHED_CALLS = ([(250, 250, 128, 0), (4091, 4091, 4091, 0), (300, 200, 150, 0)]
+DISPATCHED_CALLS = ([(250, 250, 128, 0), (4091, 4091, 4091, 0), (300, 200, 150, 0), (2560, 2560, 1536, 0), (3584, 3584, 1024, 3)]
                     + [(M, N, K, layout) for layout in (2, 3)
                        for (M, N, K) in [(300, 200, 150), (96, 1000, 4100), (1536, 1536, 64)]])
 
