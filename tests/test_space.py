@@ -44,6 +44,25 @@ def test_config_check_agrees_with_oracle_on_the_raw_product():
             assert (b.sgemm_config_check(b.make_config(*cfg)) == 0) == so.valid(cfg), cfg
 
 
+def test_tile_edges_with_odd_factors_agree_with_the_oracle():
+    """Edges of 3, 5 and 7 times a power of two are tile sizes, other multiples of 8 are not; the
+    library and the oracle draw the line at the same place and agree on everything behind it."""
+    edges = [40, 48, 56, 72, 80, 88, 96, 104, 112, 120, 144, 160, 176, 192, 208, 224, 240, 320, 448]
+    assert [e for e in edges if so.tile_edge_ok(e)] == [40, 48, 56, 80, 96, 112, 160, 192, 224, 320, 448]
+    rng = np.random.default_rng(7)
+    seen_valid = 0
+    for _ in range(3000):
+        cfg = (int(rng.choice(edges)), int(rng.choice(edges)), int(rng.choice([32, 64])), int(rng.choice([8, 16, 32])),
+               int(rng.choice([8, 16, 32])), 4, 4, 1, 1, int(rng.integers(2)), int(rng.choice([8, 16])),
+               int(rng.choice([1, 2])), int(rng.integers(2)), int(rng.choice([1, 2, 4])), 2, int(rng.choice([1, 2, 4])))
+        ok = b.sgemm_config_check(b.make_config(*cfg)) == 0
+        assert ok == so.valid(cfg), cfg
+        seen_valid += ok
+    assert seen_valid > 15          # most of the list is not a tile size, or no wave tile fits
+    for cfg in [(160, 160, 32, 16, 16, 4, 4, 1, 1, 1, 8, 2, 1, 1, 2, 1), (224, 224, 32, 16, 16, 4, 4, 1, 1, 1, 8, 2, 1, 1, 2, 1)]:
+        assert so.valid(cfg) and b.sgemm_config_check(b.make_config(*cfg)) == 0      # the built-in templates
+
+
 def test_every_emitted_config_meets_the_device_limits():
     for preset in (b.SPACE_FULL, b.SPACE_MFMA, b.SPACE_EXT, b.SPACE_DIRECT, b.SPACE_KSPLIT):
         n = b.sgemm_space_size(preset)
