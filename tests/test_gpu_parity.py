@@ -463,6 +463,18 @@ def test_largest_benchmark_sizes_sampled(workload, rows, cols):
     _sampled_check(workload, None, entry="tuned", rows=rows, cols=cols)
 
 
+@pytest.mark.parametrize("size", [512, 1024])
+def test_power_of_two_sizes_of_the_committed_table(size):
+    """512^3 and 1024^3 have entries of their own (winners of focused full searches): the
+    dispatch takes them, and the result holds against the oracle with and without the old C."""
+    tuned = b.sgemm_config_get(size, size, size, 0)
+    assert tuned is not None and b.sgemm_config_select(size, size, size, 0).as_tuple() == tuned.as_tuple()
+    A, B, C = synth.make_inputs(size, size, size, 0, seed=63)
+    for alpha, beta in [(1.0, 0.0), (-1.5, 0.75)]:
+        got = gu.run_gpu(None, A, B, C, alpha, beta, 0, entry="tuned")
+        gu.check_against_oracle(got, A, B, C, alpha, beta, 0, what=f"{size}^3 {tuned} beta {beta}")
+
+
 # ---- the tuner and the dispatch entry points on the device ---------------------------------
 
 def _restore_cache():
