@@ -395,6 +395,7 @@ int pad_workspace_for(hipStream_t s, size_t floats, float **out) {
 
 SplitPlan plan_split(const sgemm_config &cfg, int K) {
     const int slabs = (K + cfg.kwg - 1) / cfg.kwg;
+    if (slabs <= 0) return SplitPlan{1, K}; // nothing to sum, nothing to split
     int parts = std::max(1, std::min(cfg.sk, slabs));
     const int chunk_slabs = (slabs + parts - 1) / parts;
     parts = (slabs + chunk_slabs - 1) / chunk_slabs; // no empty parts

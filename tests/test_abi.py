@@ -147,6 +147,11 @@ def test_default_configuration_is_valid_and_sized_to_the_problem():
                 assert c.mfma in (1, 2) and c.sa == c.sb == 1
                 nbytes, parts, chunk = b.sgemm_config_workspace_bytes(c, M, N, K)
                 assert 1 <= parts <= 16
+    # degenerate sizes get an answer too (a call with K = 0 or an empty C launches no variant at all)
+    for shape in [(0, 0, 0), (5, 7, 0), (0, 9, 100), (1, 1, 1)]:
+        c = b.sgemm_config_default(*shape)
+        assert b.sgemm_config_check(c) == 0 and b.sgemm_config_select(*shape, 2).as_tuple() == c.as_tuple()
+        assert b.sgemm_config_workspace_bytes(c, *shape)[1] == 1
     # whole rounds of 256 workgroups where the size allows it
     assert b.sgemm_config_default(4096, 4096, 4096).mwg == 256
     assert b.sgemm_config_default(3000, 3000, 3000).mwg == 192        # 16 x 16 tiles
