@@ -175,7 +175,8 @@ typedef struct tune_result {
 /* ---- the GEMM call ------------------------------------------------------------------
  * C = alpha * op(A) * op(B) + beta * C   (first equation of the matrix-multiplication case
  * study; `layout` says how A and B are stored, see above).
- * M, N, K >= 0.  M == 0 or N == 0: no-op.  K == 0 or alpha == 0: C = beta * C and A, B are
+ * 0 <= M, N, K <= 2^31 - 1025 (a size rounded up to a tile edge stays an int), else
+ * SGEMM_E_BADARG.  M == 0 or N == 0: no-op.  K == 0 or alpha == 0: C = beta * C and A, B are
  * not read.  beta == 0: C is written without being read, so NaN/Inf in it do not propagate.
  * The variant is the cached best configuration for (M,N,K,layout).  On a miss the nearest tuned
  * shape of the same layout (every size within about a factor of 1.5) lends its configuration if

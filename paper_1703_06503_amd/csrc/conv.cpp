@@ -156,7 +156,10 @@ ConvVariant resolve(const conv2d_config &cfg, int X, int Y, int Xf, int Yf, cons
 }
 
 int check_args(int X, int Y, int Xf, int Yf, const float *F, const float *A, int lda, const float *B, int ldb) {
-    if (X < 0 || Y < 0 || !filter_ok(Xf, Yf)) { set_error("negative size or filter outside 1..31"); return SGEMM_E_BADARG; }
+    if (X < 0 || Y < 0 || X > kMaxSize || Y > kMaxSize || !filter_ok(Xf, Yf)) {
+        set_error("size negative or above 2^31 - 1025, or filter outside 1..31");
+        return SGEMM_E_BADARG;
+    }
     if (X == 0 || Y == 0) return SGEMM_OK;
     if (!F || !A || !B) { set_error("null operand"); return SGEMM_E_BADARG; }
     if (lda < X + Xf - 1 || ldb < X) { set_error("leading dimension too small (lda >= X + Xf - 1, ldb >= X)"); return SGEMM_E_BADARG; }

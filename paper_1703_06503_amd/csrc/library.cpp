@@ -109,7 +109,9 @@ int load_cache_file_locked(const char *path) {
                                     &p[6], &p[7], &p[8], &p[9], &p[10], &p[11], &p[12], &p[13], &p[14], &p[15]);
         if (got < 18 || got > 21) continue;
         sgemm_config c = from_point(p);
-        if (violates_structure(c) || M < 0 || N < 0 || K < 0 || layout < 0 || layout > 3) continue;
+        if (violates_structure(c) || M < 0 || N < 0 || K < 0 || M > kMaxSize || N > kMaxSize || K > kMaxSize || layout < 0 ||
+            layout > 3)
+            continue;
         g_tuned[ShapeKey{M, N, K, layout}] = Tuned{c, ms};
         ++added;
     }
@@ -266,7 +268,7 @@ int select_config_locked(int M, int N, int K, int layout, sgemm_config *out) {
 
 int check_gemm_args(int M, int N, int K, const float *A, int lda, const float *B, int ldb,
                     const float *C, int ldc, int layout, bool need_ab) {
-    if (M < 0 || N < 0 || K < 0) return SGEMM_E_BADARG;
+    if (M < 0 || N < 0 || K < 0 || M > kMaxSize || N > kMaxSize || K > kMaxSize) return SGEMM_E_BADARG;
     if (layout < 0 || layout > 3) return SGEMM_E_BADARG;
     if (M == 0 || N == 0) return SGEMM_OK;
     if (!C || ldc < N) return SGEMM_E_BADARG;
@@ -841,7 +843,8 @@ static_assert(sgemm_util::kScratchFloats * sizeof(float) == SGEMM_NOALLOC_SCRATC
 
 int sgemm_config_prefers_padding(const sgemm_config *cfg, int M, int N, int K, int lda, int ldb, int ldc,
                                  int layout, float beta) {
-    if (!cfg || M < 0 || N < 0 || K < 0 || layout < 0 || layout > 3) return SGEMM_E_BADARG;
+    if (!cfg || M < 0 || N < 0 || K < 0 || M > kMaxSize || N > kMaxSize || K > kMaxSize || layout < 0 || layout > 3)
+        return SGEMM_E_BADARG;
     if (violates_structure(*cfg)) return SGEMM_E_INVALID;
     const float *aligned = reinterpret_cast<const float *>(uintptr_t{256});
     return prefers_padding(*cfg, M, N, K, aligned, lda, aligned, ldb, aligned, ldc, layout, 1.0f, beta) ? 1 : 0;
@@ -1029,7 +1032,7 @@ int sgemm_config_lds_bytes(const sgemm_config *cfg) {
 
 long long sgemm_config_workspace_bytes(const sgemm_config *cfg, int M, int N, int K, int *parts,
                                        int *k_chunk) {
-    if (!cfg || M < 0 || N < 0 || K < 0) return SGEMM_E_BADARG;
+    if (!cfg || M < 0 || N < 0 || K < 0 || M > kMaxSize || N > kMaxSize || K > kMaxSize) return SGEMM_E_BADARG;
     if (violates_structure(*cfg)) return SGEMM_E_INVALID;
     const SplitPlan plan = plan_split(*cfg, K);
     if (parts) *parts = plan.parts;
@@ -1038,7 +1041,8 @@ long long sgemm_config_workspace_bytes(const sgemm_config *cfg, int M, int N, in
 }
 
 int sgemm_config_default(int M, int N, int K, int layout, sgemm_config *out) {
-    if (!out || M < 0 || N < 0 || K < 0 || layout < 0 || layout > 3) return SGEMM_E_BADARG;
+    if (!out || M < 0 || N < 0 || K < 0 || M > kMaxSize || N > kMaxSize || K > kMaxSize || layout < 0 || layout > 3)
+        return SGEMM_E_BADARG;
     *out = default_config(M, N, K);
     return SGEMM_OK;
 }
@@ -1071,7 +1075,9 @@ int sgemm_kernel_compile(const sgemm_config *cfg, int layout, int edge, sgemm_ke
 
 int sgemm_kernel_resolve(const sgemm_config *cfg, int M, int N, int K, int lda, int ldb, int ldc,
                          int layout, float beta, sgemm_config *variant, int *build) {
-    if (!cfg || !variant || !build || M <= 0 || N <= 0 || K <= 0 || layout < 0 || layout > 3) return SGEMM_E_BADARG;
+    if (!cfg || !variant || !build || M <= 0 || N <= 0 || K <= 0 || M > kMaxSize || N > kMaxSize || K > kMaxSize ||
+        layout < 0 || layout > 3)
+        return SGEMM_E_BADARG;
     if (violates_structure(*cfg)) return SGEMM_E_INVALID;
     const float *aligned = reinterpret_cast<const float *>(uintptr_t{256}); // stands for any aligned pointer
     const VariantKey key = resolve_variant(*cfg, M, N, K, aligned, lda, aligned, ldb, aligned, ldc, layout, beta);
@@ -1111,7 +1117,8 @@ int sgemm_config_get(int M, int N, int K, int layout, sgemm_config *out) {
 }
 
 int sgemm_config_set(int M, int N, int K, int layout, const sgemm_config *cfg, float ms) {
-    if (!cfg || M < 0 || N < 0 || K < 0 || layout < 0 || layout > 3) return SGEMM_E_BADARG;
+    if (!cfg || M < 0 || N < 0 || K < 0 || M > kMaxSize || N > kMaxSize || K > kMaxSize || layout < 0 || layout > 3)
+        return SGEMM_E_BADARG;
     if (violates(*cfg)) return SGEMM_E_INVALID;
     std::lock_guard<std::mutex> lock(g_mu);
     autoload_locked();
@@ -1121,7 +1128,8 @@ int sgemm_config_set(int M, int N, int K, int layout, const sgemm_config *cfg, f
 }
 
 int sgemm_config_select(int M, int N, int K, int layout, sgemm_config *out) {
-    if (!out || M < 0 || N < 0 || K < 0 || layout < 0 || layout > 3) return SGEMM_E_BADARG;
+    if (!out || M < 0 || N < 0 || K < 0 || M > kMaxSize || N > kMaxSize || K > kMaxSize || layout < 0 || layout > 3)
+        return SGEMM_E_BADARG;
     std::lock_guard<std::mutex> lock(g_mu);
     return select_config_locked(M, N, K, layout, out);
 }
@@ -1202,7 +1210,8 @@ int tune_replay(int space_id, const float *ms_table, int table_len, int strategy
 
 int tune_ex(int M, int N, int K, int layout, float alpha, float beta, int strategy, int budget,
             unsigned long long seed, const tune_opts *opts, tune_result *out) {
-    if (M <= 0 || N <= 0 || K <= 0 || layout < 0 || layout > 3) return SGEMM_E_BADARG;
+    if (M <= 0 || N <= 0 || K <= 0 || M > kMaxSize || N > kMaxSize || K > kMaxSize || layout < 0 || layout > 3)
+        return SGEMM_E_BADARG;
     if (strategy < 0 || strategy > 3) return SGEMM_E_BADARG;
     const Space *space = get_space(opts ? opts->space : SGEMM_SPACE_FULL);
     if (!space) return SGEMM_E_BADARG;

@@ -20,6 +20,8 @@ constexpr int kMaxSplitK = 64;         // upper bound of the SK parameter
 // Largest leading dimension of A and B (floats): a tile of up to 512 stored rows then spans
 // less than 2 GiB, the reach of the kernels' 32-bit byte offsets and buffer windows.
 constexpr int kMaxLeadingDim = 1 << 20;
+// M, N, K up to here: rounding a size up to a tile edge (at most 512) stays inside an int
+constexpr int kMaxSize = 0x7fffffff - 1024;
 constexpr int kMaxLoadsInFlight = 63;  // the vmcnt counter of a wave
 
 using Point = std::array<int, kDims>;

@@ -63,6 +63,18 @@ def test_bad_arguments_are_rejected_without_a_gpu():
     with pytest.raises(b.SgemmError) as e:
         b.tune_ex(4, 4, 4, 0, 1.0, 0.0, 17, 0)
     assert e.value.status == b.E_BADARG
+    # sizes so close to 2^31 that rounding them up to a tile would leave an int are refused
+    huge = 2**31 - 1
+    with pytest.raises(b.SgemmError) as e:
+        b.sgemm_tuned_on(0, huge, 4, 4, 1.0, 1, 4, 1, 4, 0.0, 1, 4, 0)
+    assert e.value.status == b.E_BADARG
+    for call in (lambda: b.sgemm_config_default(huge, 4, 4), lambda: b.sgemm_config_select(4, huge, 4, 0),
+                 lambda: b.sgemm_config_workspace_bytes(cfg, 4, 4, huge),
+                 lambda: b.sgemm_kernel_resolve(cfg, huge, 4, 4, 4, 4, 4, 0, 0.0)):
+        with pytest.raises(b.SgemmError) as e:
+            call()
+        assert e.value.status == b.E_BADARG
+    assert b.sgemm_config_check(b.sgemm_config_default(2**31 - 1025, 4, 4)) == 0      # the largest size there is
     # empty problems are fine and launch nothing
     assert b.sgemm_run_config(0, cfg, 0, 4, 4, 1.0, 0, 4, 0, 4, 0.0, 0, 4, 0) == 0
 
