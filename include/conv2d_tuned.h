@@ -62,7 +62,8 @@ int conv2d_kernel_compile(const conv2d_config *cfg, int Xf, int Yf, int edge, in
 
 /* ---- running ---------------------------------------------------------------------------
  * One convolution with the given configuration on the given HIP stream (null = default).
- * 0 <= X, Y <= 2^31 - 1025 and at most 65535 rows of workgroups, else SGEMM_E_BADARG. */
+ * 0 <= X, Y <= 2^31 - 1025 and at most 65535 rows of workgroups (Y <= 65535 * YWG * YWPT), else
+ * SGEMM_E_BADARG. */
 int conv2d_run_config(void *hip_stream, const conv2d_config *cfg, int X, int Y, int Xf, int Yf,
                       float w, const float *F, const float *A, int lda, float *B, int ldb);
 

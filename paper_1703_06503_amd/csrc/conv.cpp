@@ -307,7 +307,6 @@ int conv2d_reference(void *hip_stream, int X, int Y, int Xf, int Yf, float w, co
                      int lda, float *B, int ldb) {
     const int rc = check_args(X, Y, Xf, Yf, F, A, lda, B, ldb);
     if (rc != SGEMM_OK) return rc;
-    if (Y > 4 * 65535) { set_error("more than 65535 workgroup rows"); return SGEMM_E_BADARG; }
     const hipError_t e = sgemm_util::launch_conv2d_reference(static_cast<hipStream_t>(hip_stream), X, Y, Xf, Yf, w,
                                                              F, A, lda, B, ldb);
     if (e != hipSuccess) { set_error(std::string("reference kernel: ") + hipGetErrorString(e)); return SGEMM_E_LAUNCH; }

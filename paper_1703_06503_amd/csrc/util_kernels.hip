@@ -15,28 +15,31 @@ __global__ void reference_kernel(int M, int N, int K, float alpha, const float *
                                  int lda, const float *__restrict__ B, int ldb, float beta,
                                  float *__restrict__ C, int ldc, int layout) {
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
-    const int i = blockIdx.y * blockDim.y + threadIdx.y;
-    if (i >= M || j >= N) return;
-    double sum = 0.0;
-    if (alpha != 0.0f) {
-        for (int k = 0; k < K; ++k) {
-            const float a = (layout & 1) ? A[(size_t)k * lda + i] : A[(size_t)i * lda + k];
-            const float b = (layout & 2) ? B[(size_t)j * ldb + k] : B[(size_t)k * ldb + j];
-            sum += (double)a * (double)b;
+    if (j >= N) return;
+    // rows are strided over the grid: the host caps the number of workgroup rows
+    for (long long i = (long long)blockIdx.y * blockDim.y + threadIdx.y; i < M; i += (long long)gridDim.y * blockDim.y) {
+        double sum = 0.0;
+        if (alpha != 0.0f) {
+            for (int k = 0; k < K; ++k) {
+                const float a = (layout & 1) ? A[(size_t)k * lda + i] : A[(size_t)i * lda + k];
+                const float b = (layout & 2) ? B[(size_t)j * ldb + k] : B[(size_t)k * ldb + j];
+                sum += (double)a * (double)b;
+            }
         }
+        double r = (double)alpha * sum;
+        float *p = C + (size_t)i * ldc + j;
+        if (beta != 0.0f) r += (double)beta * (double)*p;
+        *p = (float)r;
     }
-    double r = (double)alpha * sum;
-    float *p = C + (size_t)i * ldc + j;
-    if (beta != 0.0f) r += (double)beta * (double)*p;
-    *p = (float)r;
 }
 
 __global__ void scale_kernel(int M, int N, float beta, float *__restrict__ C, int ldc) {
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
-    const int i = blockIdx.y * blockDim.y + threadIdx.y;
-    if (i >= M || j >= N) return;
-    float *p = C + (size_t)i * ldc + j;
-    *p = (beta == 0.0f) ? 0.0f : beta * *p;
+    if (j >= N) return;
+    for (long long i = (long long)blockIdx.y * blockDim.y + threadIdx.y; i < M; i += (long long)gridDim.y * blockDim.y) {
+        float *p = C + (size_t)i * ldc + j;
+        *p = (beta == 0.0f) ? 0.0f : beta * *p;
+    }
 }
 
 __device__ inline unsigned long long mix64(unsigned long long z) {
@@ -201,12 +204,13 @@ __global__ void conv2d_reference_kernel(int X, int Y, int Xf, int Yf, float w,
                                         const float *__restrict__ F, const float *__restrict__ A,
                                         int lda, float *__restrict__ B, int ldb) {
     const int x = blockIdx.x * blockDim.x + threadIdx.x;
-    const int y = blockIdx.y * blockDim.y + threadIdx.y;
-    if (x >= X || y >= Y) return;
-    float acc = 0.0f;
-    for (int j = 0; j < Yf; ++j)
-        for (int i = 0; i < Xf; ++i) acc = fmaf(F[j * Xf + i], A[(size_t)(y + j) * lda + x + i], acc);
-    B[(size_t)y * ldb + x] = w * acc;
+    if (x >= X) return;
+    for (long long y = (long long)blockIdx.y * blockDim.y + threadIdx.y; y < Y; y += (long long)gridDim.y * blockDim.y) {
+        float acc = 0.0f;
+        for (int j = 0; j < Yf; ++j)
+            for (int i = 0; i < Xf; ++i) acc = fmaf(F[j * Xf + i], A[(size_t)(y + j) * lda + x + i], acc);
+        B[(size_t)y * ldb + x] = w * acc;
+    }
 }
 
 // Every element of an M x N matrix (leading dimension ld) gets the same bit pattern: the
@@ -229,6 +233,13 @@ __global__ void zero_u32_kernel(unsigned int *p, int n) {
 // this name as an address; it asks the runtime for the array's device address (below).
 static __device__ __align__(256) float scratch[sgemm_util::kScratchFloats];
 
+// The second grid dimension holds at most 65535 workgroups: kernels that put matrix rows there
+// stride over them.
+inline unsigned rows_of_workgroups(int rows, int per_workgroup) {
+    const long long g = ((long long)rows + per_workgroup - 1) / per_workgroup;
+    return (unsigned)(g > 65535 ? 65535 : g);
+}
+
 inline int grid_for(size_t n, int block) {
     size_t g = (n + block - 1) / block;
     if (g > 256 * 16) g = 256 * 16;
@@ -244,7 +255,7 @@ hipError_t launch_reference(hipStream_t s, int M, int N, int K, float alpha, con
                             int lda, const float *B, int ldb, float beta, float *C, int ldc,
                             int layout) {
     if (M == 0 || N == 0) return hipSuccess;
-    dim3 block(64, 4), grid((N + 63) / 64, (M + 3) / 4);
+    dim3 block(64, 4), grid((N + 63) / 64, rows_of_workgroups(M, 4));
     hipLaunchKernelGGL(reference_kernel, grid, block, 0, s, M, N, K, alpha, A, lda, B, ldb, beta,
                        C, ldc, layout);
     return hipGetLastError();
@@ -252,7 +263,7 @@ hipError_t launch_reference(hipStream_t s, int M, int N, int K, float alpha, con
 
 hipError_t launch_scale(hipStream_t s, int M, int N, float beta, float *C, int ldc) {
     if (M == 0 || N == 0) return hipSuccess;
-    dim3 block(64, 4), grid((N + 63) / 64, (M + 3) / 4);
+    dim3 block(64, 4), grid((N + 63) / 64, rows_of_workgroups(M, 4));
     hipLaunchKernelGGL(scale_kernel, grid, block, 0, s, M, N, beta, C, ldc);
     return hipGetLastError();
 }
@@ -334,7 +345,7 @@ hipError_t launch_conv2d_reference(hipStream_t s, int X, int Y, int Xf, int Yf, 
                                    const float *A, int lda, float *B, int ldb) {
     if (X <= 0 || Y <= 0) return hipSuccess;
     const dim3 block(64, 4);
-    hipLaunchKernelGGL(conv2d_reference_kernel, dim3((X + 63) / 64, (Y + 3) / 4), block, 0, s, X, Y,
+    hipLaunchKernelGGL(conv2d_reference_kernel, dim3((X + 63) / 64, rows_of_workgroups(Y, 4)), block, 0, s, X, Y,
                        Xf, Yf, w, F, A, lda, B, ldb);
     return hipGetLastError();
 }

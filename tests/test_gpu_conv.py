@@ -91,6 +91,15 @@ def test_reference_kernel_matches_the_oracle():
         check(run(None, A, F, -0.5, X, Y, entry="reference"), A, F, -0.5, X, Y, what="reference")
 
 
+def test_more_image_rows_than_one_grid_dimension_holds():
+    """270 000 image rows: the reference kernel strides over the rows that its grid's second
+    dimension (at most 65 535 workgroups) does not hold; the tuned variant's tile rows fit."""
+    X, Y, Xf, Yf = 16, 270000, 3, 3
+    A, F = synth.make_conv_inputs(X, Y, Xf, Yf, seed=51)
+    for entry in ("reference", "tuned"):
+        check(run(None, A, F, 0.25, X, Y, entry=entry), A, F, 0.25, X, Y, what=f"{entry}, {Y} rows")
+
+
 def test_default_dispatch_for_filter_sizes_that_were_never_tuned():
     """conv2d_tuned with nothing in its table: the built-in defaults for small, medium, large and
     very large filters, square and not, on a ragged image."""

@@ -354,6 +354,24 @@ def test_degenerate_sizes():
     assert e.value.status == b.E_INVALID
 
 
+def test_more_rows_than_one_grid_dimension_holds():
+    """300 000 rows: the reference kernel and the scaling kernel put rows into the grid's second
+    dimension (at most 65 535 workgroups there) and stride over what does not fit; the tuned
+    variants number their tiles along the first."""
+    import torch
+    M, N, K = 300000, 24, 40
+    A, B, C = synth.make_inputs(M, N, K, 0, seed=64)
+    ref = orc.sgemm(1.5, A, B, 0.5, C, 0)
+    for entry in ("reference", "tuned"):
+        got = gu.run_gpu(None, A, B, C, 1.5, 0.5, 0, entry=entry)
+        gu.check_against_oracle(got, A, B, C, 1.5, 0.5, 0, ref, what=f"{entry} {M}x{N}x{K}")
+    # alpha = 0: C = beta * C, every row of it
+    dC = torch.from_numpy(C.copy()).cuda()
+    b.sgemm_tuned_on(None, M, N, K, 0.0, None, K, None, N, 0.5, dC, N, 0)
+    torch.cuda.synchronize()
+    assert np.array_equal(dC.cpu().numpy(), np.float32(0.5) * C)
+
+
 def test_reference_kernel_against_oracle():
     """The device reference kernel that tune() verifies against is itself held to the oracle."""
     for layout in range(4):

@@ -94,7 +94,7 @@ ODD_EDGE_CONFIGS = [b.make_config(160, 160, 32, 16, 16, 4, 4, 1, 1, 1, 8, 2, 1),
 ODD_EDGE_SHAPES = [(1120, 1120, 128), (333, 500, 200)]     # a multiple of every such tile, and a ragged one
 
 # (M, N, K, layout) of calls that go through the dispatch without an exactly tuned shape
-DISPATCHED_CALLS = ([(250, 250, 128, 0), (4091, 4091, 4091, 0), (300, 200, 150, 0), (2560, 2560, 1536, 0), (3584, 3584, 1024, 3)]
+DISPATCHED_CALLS = ([(250, 250, 128, 0), (4091, 4091, 4091, 0), (300, 200, 150, 0), (2560, 2560, 1536, 0), (3584, 3584, 1024, 3), (300000, 24, 40, 0)]
                     + [(M, N, K, layout) for layout in (2, 3)
                        for (M, N, K) in [(300, 200, 150), (96, 1000, 4100), (1536, 1536, 64)]])
 
