@@ -393,6 +393,7 @@ int ktuner_tune(ktuner *t, int strategy, int budget, unsigned long long seed, co
             std::memcpy(&refmax, &bits, 4);
             abs_tols.push_back(t->abs_tol >= 0.0f ? t->abs_tol : 1e-6f * refmax);
         }
+        (void)hipStreamSynchronize(s); // before rk, and with it the reference kernel's module, goes away
     }
     const float rel_tol = t->rel_tol >= 0.0f ? t->rel_tol : 1e-5f;
 
