@@ -147,8 +147,8 @@ struct SplitPlan {
 // A workgroup of a template sustains `eff` of a CU's matrix peak while it runs and a launch
 // costs `fix_us` on top (launch, first slab, epilogue); the 256 CUs take ceil(workgroups / 256)
 // workgroups each, so what decides is how the tile grid quantises the problem.  `eff` and
-// `fix_us` were fitted to 22 measured shapes from 384^3 to 7168^3, skinny ones included (the
-// model's pick was the fastest template on 15 of them and at most 10 % behind on the rest);
+// `fix_us` were fitted to 27 measured shapes from 300 x 200 x 150 to 7168^3, skinny ones included
+// (the model's pick was the fastest template on 21 of them and at most 5 % behind on the rest);
 // the 160- and 224-wide tiles were added afterwards, from two shapes each.
 // `pairs`: two workgroups of the template fit a CU and hide each other's stalls; a lone one
 // reaches 0.93 of `eff`.  `max_sk`: split K is considered for the template.
@@ -159,17 +159,17 @@ struct Template {
     int max_sk;
 };
 const Template kTemplates[] = {
-    {32, 32, 64, 16, 16, 8, 2, 0, 2, 0.620, 5.6, false, 1},
-    {64, 64, 64, 16, 16, 8, 1, 1, 2, 0.816, 4.1, true, 16},
-    {64, 64, 128, 32, 32, 32, 2, 1, 1, 0.736, 4.4, false, 1},
-    {96, 96, 64, 16, 16, 8, 2, 1, 2, 0.790, 5.0, false, 1},
-    {128, 64, 32, 16, 16, 8, 1, 0, 1, 0.837, 4.8, false, 1},
-    {128, 128, 64, 16, 32, 8, 1, 1, 1, 0.904, 6.6, false, 16},
+    {32, 32, 64, 16, 16, 8, 2, 0, 2, 0.603, 4.0, false, 1},
+    {64, 64, 64, 16, 16, 8, 1, 1, 2, 0.821, 4.4, true, 16},
+    {64, 64, 128, 32, 32, 32, 2, 1, 1, 0.737, 3.7, false, 1},
+    {96, 96, 64, 16, 16, 8, 2, 1, 2, 0.784, 3.9, false, 1},
+    {128, 64, 32, 16, 16, 8, 1, 0, 1, 0.829, 4.2, false, 1},
+    {128, 128, 64, 16, 32, 8, 1, 1, 1, 0.906, 6.6, false, 16},
     {160, 160, 32, 16, 16, 8, 2, 1, 1, 0.860, 22.4, false, 1}, // (two shapes each: 2560^3 and
-    {192, 192, 32, 16, 32, 8, 2, 0, 1, 0.898, 8.6, false, 1},
+    {192, 192, 32, 16, 32, 8, 2, 0, 1, 0.897, 6.4, false, 1},
     {224, 224, 32, 16, 16, 8, 2, 1, 1, 0.895, 14.6, false, 1}, //  5120^3, 3584^3 and 7168^3)
-    {256, 128, 32, 16, 32, 8, 1, 1, 1, 0.908, 5.7, false, 1},
-    {256, 256, 32, 16, 32, 8, 1, 0, 1, 0.943, 9.1, false, 1},
+    {256, 128, 32, 16, 32, 8, 1, 1, 1, 0.908, 5.6, false, 1},
+    {256, 256, 32, 16, 32, 8, 1, 0, 1, 0.943, 8.8, false, 1},
 };
 constexpr double kCus = 256.0;
 constexpr double kCuFlopPerUs = 614400.0;     // 256 FLOP per clock at 2.4 GHz
