@@ -326,6 +326,26 @@ def sgemm_tuned_on(stream, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, layout=
                                        ldb, beta, _ptr(C), ldc, layout), "sgemm_tuned_on")
 
 
+def sgemm_tuned_prepare(stream, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, layout=0, noalloc=False):
+    """A callable that repeats this sgemm_tuned_on() (or sgemm_tuned_noalloc()) call with its
+    arguments marshalled once: the stream handle and the device addresses are read now, so the
+    tensors must stay alive and in place.  For loops in which the microseconds that looking
+    them up costs per call would show (kernels of a few microseconds)."""
+    fn = lib().sgemm_tuned_noalloc if noalloc else lib().sgemm_tuned_on
+    what = "sgemm_tuned_noalloc" if noalloc else "sgemm_tuned_on"
+    args = (ctypes.c_void_p(_stream(stream)), ctypes.c_int(M), ctypes.c_int(N), ctypes.c_int(K),
+            ctypes.c_float(alpha), ctypes.c_void_p(_ptr(A)), ctypes.c_int(lda), ctypes.c_void_p(_ptr(B)),
+            ctypes.c_int(ldb), ctypes.c_float(beta), ctypes.c_void_p(_ptr(C)), ctypes.c_int(ldc),
+            ctypes.c_int(layout))
+
+    def call():
+        status = fn(*args)
+        if status < 0:
+            raise SgemmError(status, what)
+        return status
+    return call
+
+
 def sgemm_tuned_noalloc(stream, M, N, K, alpha, A, lda, B, ldb, beta, C, ldc, layout=0):
     return _check(lib().sgemm_tuned_noalloc(_stream(stream), M, N, K, alpha, _ptr(A), lda, _ptr(B),
                                             ldb, beta, _ptr(C), ldc, layout), "sgemm_tuned_noalloc")

@@ -75,6 +75,11 @@ def test_bad_arguments_are_rejected_without_a_gpu():
             call()
         assert e.value.status == b.E_BADARG
     assert b.sgemm_config_check(b.sgemm_config_default(2**31 - 1025, 4, 4)) == 0      # the largest size there is
+    # a prepared call (arguments marshalled once) reports what the ordinary call reports
+    with pytest.raises(b.SgemmError) as e:
+        b.sgemm_tuned_prepare(0, -1, 4, 4, 1.0, 0, 4, 0, 4, 0.0, 0, 4, 0)()
+    assert e.value.status == b.E_BADARG
+    assert b.sgemm_tuned_prepare(0, 0, 4, 4, 1.0, 0, 4, 0, 4, 0.0, 0, 4, 0)() == 0
     # empty problems are fine and launch nothing
     assert b.sgemm_run_config(0, cfg, 0, 4, 4, 1.0, 0, 4, 0, 4, 0.0, 0, 4, 0) == 0
 

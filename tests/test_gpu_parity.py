@@ -708,6 +708,24 @@ def test_online_tuning_with_concurrent_callers_of_one_shape():
         _restore_cache()
 
 
+def test_prepared_call_repeats_the_ordinary_one():
+    """The binding's prepared call (arguments marshalled once) launches what sgemm_tuned_on()
+    launches: same bits, call after call, also after the output was overwritten in between."""
+    import torch
+    M, N, K = 300, 200, 150
+    A, B, C = synth.make_inputs(M, N, K, 0, seed=76)
+    dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    want = gu.run_gpu(None, A, B, C, 1.25, 0.0, 0, entry="tuned")
+    gu.check_against_oracle(want, A, B, C, 1.25, 0.0, 0)
+    dC = torch.empty((M, N), dtype=torch.float32, device="cuda")
+    call = b.sgemm_tuned_prepare(None, M, N, K, 1.25, dA, K, dB, N, 0.0, dC, N, 0)
+    for _ in range(3):
+        dC.fill_(float("nan"))
+        assert call() == 0
+        torch.cuda.synchronize()
+        assert np.array_equal(dC.cpu().numpy(), want)
+
+
 def test_launch_on_a_side_stream_and_on_the_set_stream():
     import torch
     cfg = _some_configs()[1]
